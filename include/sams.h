@@ -1,0 +1,148 @@
+/*
+ * sams.h -- C ABI of the MI355X (gfx950) hot path of SketchedAMSGrad with gradient
+ * averaging (Algorithm 2 of arXiv 2210.07454): per optimisation step, the n workers'
+ * error-compensated momentum vectors are Count-Sketched, the sketches averaged, every
+ * coordinate recovered (median over rows, scaled by 1/sqrt(vhat)), the k largest
+ * selected, their exact values gathered, and the AMSGrad state updated.  The n workers
+ * are batched buffers on one GPU.
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers into caller-owned memory (fp32 unless said
+ *     otherwise), 16-byte aligned, row-major with the shapes given, non-overlapping unless
+ *     "in place" is stated.  Only `hash_host` of sams_create is a HOST pointer.
+ *   - Work is enqueued on the hipStream_t given to sams_create and is asynchronous with
+ *     respect to the host; no entry point synchronises the host with the device.  Calls on one
+ *     context must be issued from one host thread at a time; a context's scratch is shared
+ *     by its calls, which the stream orders.
+ *   - The library never frees or retains caller memory beyond the call, except that
+ *     amsgrad_ef_update records the selected index set in the context (a bitmap) for
+ *     the next call's second-moment update.
+ *   - Return value: SAMS_OK, or a negative code.  SAMS_EINVAL: a null or misaligned pointer,
+ *     or a size outside the documented range -- nothing was enqueued.  SAMS_ENOMEM: the
+ *     context's scratch could not be allocated.  SAMS_EHIP: the HIP runtime reported an error
+ *     (sams_last_hip_error() returns its hipError_t value).
+ *   - Non-finite inputs are not detected; NaNs make the ordering of the selection undefined.
+ *   - Coordinates are 0-based; d < 2^31 - 1 (the hash modulus).
+ */
+#ifndef SAMS_H
+#define SAMS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAMS_OK 0
+#define SAMS_EINVAL (-1)
+#define SAMS_ENOMEM (-2)
+#define SAMS_EHIP (-3)
+
+#define SAMS_MAX_ROWS 16
+
+typedef struct sams_ctx sams_ctx;
+
+/*
+ * Create a context for d coordinates, n workers, an r x c Count Sketch and k selected
+ * coordinates per step.
+ *   hash_host  HOST pointer to r*4 uint32: per row (a_h, b_h, a_s, b_s).  The bucket hash of row j is
+ *              h_j(l) = ((a_h*l + b_h) mod (2^31-1)) mod c and the sign hash is s_j(l) = +1 if
+ *              ((a_s*l + b_s) mod (2^31-1)) is even, -1 if odd (the paper, Sec. II-C, only asks for
+ *              "bucket hashes" and "sign hashes"; this 2-universal family is this library's choice).
+ *              Requires 1 <= a < 2^31-1, 0 <= b < 2^31-1.  The values are copied.
+ *   hip_stream the hipStream_t (as void*) every later call on this context is enqueued on; NULL =
+ *              the default stream.
+ * Ranges: 1 <= d < 2^31-1, 1 <= n <= 1024, 1 <= r <= SAMS_MAX_ROWS, 1 <= c < 2^31-1, 1 <= k <= d.
+ * Allocates the context's device scratch (about 4d bytes for the estimates, d/8 for the index bitmap,
+ * plus small selection state); sams_scratch_bytes reports the total.
+ * For an even r the median of Sec. II-C is the lower middle element.
+ */
+int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int64_t k,
+                const uint32_t *hash_host, void *hip_stream);
+
+/* Waits for the context's stream, frees its scratch and the context.  NULL is a no-op. */
+int sams_destroy(sams_ctx *ctx);
+
+/* Device bytes the context allocated. */
+int64_t sams_scratch_bytes(const sams_ctx *ctx);
+
+/* hipError_t of the most recent failure reported as SAMS_EHIP by this process (0 if none). */
+int sams_last_hip_error(void);
+
+/*
+ * Writes h_j(l) and s_j(l) for every row and coordinate (the hash functions of Sec. II-C as defined
+ * under sams_create), so that they can be compared one by one with another implementation.
+ *   bucket  [r][d] int32, device, out     sign  [r][d] int8 (+1 / -1), device, out
+ */
+int sams_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
+
+/*
+ * Stage 1 -- Count Sketch of every worker's vector (Sec. II-C update rule; Alg. 2 worker line
+ * "Sketch S_t^(i) = S(m_t^(i) + (alpha_{t-1}/alpha_t) e_{t-1}^(i))"):
+ *     S_workers[i][j][h_j(l)] += s_j(l) * u[i][l]      for all workers i, rows j, coordinates l.
+ *   u          [n][d] in    the vectors to sketch (what amsgrad_ef_update leaves in e_u)
+ *   S_workers  [n][r][c] out, overwritten (zeroed by the call, then accumulated)
+ * The order in which the terms of one bucket are added is not specified (fp32 rounding may differ
+ * from a sequential sum in the last bits); on inputs whose partial sums are exact the result is exact.
+ */
+int sketch_accumulate(sams_ctx *ctx, const float *u, float *S_workers);
+
+/*
+ * Stage 2 -- aggregation on the master (Alg. 2: "Aggregate S_t = 1/n sum_i S_t^(i)"; linearity, Eq. 3):
+ *     S_mean[j][b] = (S_workers[0][j][b] + S_workers[1][j][b] + ... ) / n, workers added in ascending i.
+ *   S_workers [n][r][c] in     S_mean [r][c] out
+ */
+int sketch_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean);
+
+/*
+ * Stage 3 -- heavy-coordinate recovery and selection (Sec. II-C unsketch; Alg. 3; Alg. 2 master line
+ * "Unsketch Delta_t = Top-k(U(S_t, vhat_t))"):
+ *     est[l] = median_j( s_j(l) * S_mean[j][h_j(l)] ) / sqrt(vhat[l])        for every l < d
+ *     idx    = the k coordinates with the largest |est|, ties going to the smaller coordinate,
+ *              written in ascending order.
+ * Alg. 3 is read as this per-coordinate scaling (its result must equal sketching vhat^{-1/2}(m + e) and
+ * unsketching normally, as the text under Alg. 2 says).
+ *   S_mean  [r][c] in        vhat  [d] in, strictly positive; NULL = plain operator U_0 (no scaling, Alg. 1)
+ *   idx     [k] int32 out    est_sel [k] out or NULL: est at the selected coordinates
+ */
+int unsketch_topk(sams_ctx *ctx, const float *S_mean, const float *vhat, int32_t *idx, float *est_sel);
+
+/* The recovery half of stage 3 alone: est [d] out (all coordinates).  For inspection and tests. */
+int unsketch_estimates(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
+
+/*
+ * Stage 4 -- second round (Sec. III-A; definition of Delta_t^(i) and Delta_t under Alg. 2): exact values of
+ * the selected coordinates from every worker, averaged and scaled,
+ *     U_workers[i][q] = u[i][idx[q]] ;   delta[q] = ((sum_i U_workers[i][q]) / n) / sqrt(vhat[idx[q]])
+ * (workers added in ascending i; vhat == NULL skips the scaling).
+ *   u [n][d] in   vhat [d] in or NULL   idx [k] int32 in (each < d)   U_workers [n][k] out   delta [k] out
+ */
+int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx, float *U_workers,
+                float *delta);
+
+/*
+ * Stage 5 -- AMSGrad update with error feedback (Alg. 2).  One call finishes iteration t and starts
+ * iteration t+1:
+ *   finish t ("tail"; lines for e_t and x_{t+1}; e_t is zero on I_t as the proof of Lemma 3 states),
+ *   if k_sel > 0:
+ *       e_u[i][idx[q]] = 0 for all i ;   x[idx[q]] -= lr * delta[q] ;   I_t = {idx[q]} is recorded.
+ *   start t+1 ("head"; lines for m, h, v, vhat and the vector to sketch), if g_next != NULL:
+ *       m[i][l]   = beta1 * m[i][l] + (1-beta1) * g_next[i][l]
+ *       e_u[i][l] = m[i][l] + ef_ratio * e_u[i][l]                       (now holds u_{t+1}^(i))
+ *       h[l]      = (sum_i g_next[i][l]) / n  if l in I_t, else 0
+ *       v[l]      = beta2 * v[l] + (1-beta2) * h[l]^2 ;   vhat[l] = max(vhat[l], v[l])
+ *   (v decays on every coordinate, as the algorithm box writes it.)
+ * The first call of a run passes k_sel = 0 (I_0 is empty: head only); the last may pass g_next = NULL.
+ *   g_next [n][d] in or NULL     m, e_u [n][d] in place     v, vhat, x [d] in place
+ *   idx [k_sel] int32 in, strictly ascending, each < d;  delta [k_sel] in;  0 <= k_sel <= k
+ *   ef_ratio = alpha_{t}/alpha_{t+1} (1 for a constant step size)
+ * Initial state per Alg. 2: m = e_u = 0, v = vhat = eps (a positive constant), x = x_1.
+ */
+int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, float *v, float *vhat,
+                      float *x, const int32_t *idx, const float *delta, int64_t k_sel, float beta1,
+                      float beta2, float lr, float ef_ratio);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMS_H */

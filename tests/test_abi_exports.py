@@ -1,0 +1,58 @@
+"""The C-ABI library loads and exports every symbol include/sams.h declares (no GPU work here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch  # noqa: F401  (loads the HIP runtime the library binds to)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sams.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"^\s*(?:int|int64_t)\s+(\w+)\s*\(", text, flags=re.M)
+
+
+def test_header_declares_the_five_stage_calls():
+    names = declared_functions()
+    for want in ("sketch_accumulate", "sketch_reduce", "unsketch_topk", "gather_topk", "amsgrad_ef_update",
+                 "sams_create", "sams_destroy"):
+        assert want in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2210_07454_amd import sams
+    lib = sams.load()
+    names = declared_functions()
+    assert sorted(names) == sorted(sams.EXPORTS)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_argument_validation_needs_no_gpu():
+    from paper_2210_07454_amd import sams
+    lib = sams.load()
+    h = ctypes.c_void_p()
+    hp = np.ones((5, 4), dtype=np.uint32)
+    hpp = hp.ctypes.data_as(ctypes.c_void_p)
+    assert lib.sams_create(ctypes.byref(h), 0, 1, 5, 8, 1, hpp, None) == sams.SAMS_EINVAL        # d < 1
+    assert lib.sams_create(ctypes.byref(h), 100, 1, 17, 8, 1, hpp, None) == sams.SAMS_EINVAL     # r too large
+    assert lib.sams_create(ctypes.byref(h), 100, 1, 5, 8, 101, hpp, None) == sams.SAMS_EINVAL    # k > d
+    assert lib.sams_create(ctypes.byref(h), 100, 1, 5, 8, 1, None, None) == sams.SAMS_EINVAL     # no hashes
+    assert lib.sams_create(ctypes.byref(h), 2**31 - 1, 1, 5, 8, 1, hpp, None) == sams.SAMS_EINVAL
+    hp[3, 0] = 0
+    assert lib.sams_create(ctypes.byref(h), 100, 1, 5, 8, 1, hpp, None) == sams.SAMS_EINVAL      # a = 0
+    assert h.value is None
+    assert lib.sams_destroy(None) == sams.SAMS_OK
+    assert lib.sketch_accumulate(None, None, None) == sams.SAMS_EINVAL
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    from paper_2210_07454_amd import sams
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        sams.Context(100, 1, 5, 8, 1, np.ones((5, 4), dtype=np.uint32))

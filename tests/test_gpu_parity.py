@@ -1,0 +1,333 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  Integer work (hashes, signs, index sets) must match bit for bit; floating
+results must match within 1e-5 relative (tables: relative to the absolute mass of the bucket).
+
+Each stage is fed the oracle's bit-identical inputs for that stage ("stage-isolated"); the chained
+tests then let the GPU run freely and re-derive every step from the GPU's own previous state.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import Oracle
+from paper_2210_07454_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def sams():
+    from paper_2210_07454_amd import sams as mod
+    mod.load()
+    return mod
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def abs_mass(u, hp, c):
+    """A[i][j][b] = sum of |u[i][l]| over the coordinates of bucket b of row j (fp64)."""
+    n, d = u.shape
+    bkt, _ = oracle.hash_dump(hp, c, d)
+    A = np.zeros((n, hp.shape[0], c))
+    for i in range(n):
+        for j in range(hp.shape[0]):
+            A[i, j] = np.bincount(bkt[j], weights=np.abs(u[i]).astype(np.float64), minlength=c)
+    return A
+
+
+SHAPES = [  # d, n, r, c, k  -- several tiles, ragged tails, non-power-of-two c, even r, extremes
+    (65_536, 4, 5, 2_048, 256),
+    (100_003, 3, 5, 1_000, 777),
+    (70_001, 2, 10, 400, 500),
+    (33, 1, 1, 1, 1),
+    (5_000, 2, 16, 7, 5_000),
+    (262_144, 8, 7, 100_000, 3_000),
+    (4_100, 5, 3, 8_191, 1),
+]
+
+
+@pytest.mark.parametrize("d,n,r,c,k", SHAPES)
+def test_hash_indices_and_signs_bit_exact(sams, d, n, r, c, k):
+    hp = inputs.hash_params(r, seed=d % 97)
+    with sams.Context(d, n, r, c, k, hp) as ctx:
+        b = torch.empty((r, d), device="cuda", dtype=torch.int32)
+        s = torch.empty((r, d), device="cuda", dtype=torch.int8)
+        ctx.sams_hash_dump(b, s)
+        bo, so = oracle.hash_dump(hp, c, d)
+        assert np.array_equal(host(b), bo)
+        assert np.array_equal(host(s), so)
+
+
+def test_hash_extreme_parameters_bit_exact(sams):
+    P = inputs.P31
+    hp = np.array([[P - 1, P - 1, P - 1, P - 1], [1, 0, 1, P - 1], [P - 1, 0, 2, 1], [46341, P - 2, P - 2, 5]],
+                  dtype=np.uint32)
+    d, c = 300_001, 99_991
+    with sams.Context(d, 1, 4, c, 1, hp) as ctx:
+        b = torch.empty((4, d), device="cuda", dtype=torch.int32)
+        s = torch.empty((4, d), device="cuda", dtype=torch.int8)
+        ctx.sams_hash_dump(b, s)
+        bo, so = oracle.hash_dump(hp, c, d)
+        assert np.array_equal(host(b), bo) and np.array_equal(host(s), so)
+
+
+@pytest.mark.parametrize("d,n,r,c,k", SHAPES)
+def test_sketch_accumulate_integer_inputs_bit_exact(sams, d, n, r, c, k):
+    hp = inputs.hash_params(r, seed=3)
+    amax = 64 if d * 64 < (1 << 24) else max(1, (1 << 23) // d)
+    u = inputs.integer_vectors(n, d, amax=amax, seed=d).numpy()
+    o = Oracle("f32")
+    want = np.stack([o.sketch(u[i], hp, c) for i in range(n)])
+    with sams.Context(d, n, r, c, k, hp) as ctx:
+        S = torch.full((n, r, c), 7.0, device="cuda")          # must be overwritten, not accumulated into
+        ctx.sketch_accumulate(dev(u), S)
+        assert np.array_equal(host(S), want)
+        Sm = torch.empty((r, c), device="cuda")
+        ctx.sketch_reduce(S, Sm)
+        assert np.array_equal(host(Sm), o.sketch_mean(want))
+
+
+@pytest.mark.parametrize("wl,d", [("C1", 65_536), ("C2", 300_000), ("C3", 200_000), ("C4", 500_000)])
+def test_sketch_accumulate_float_within_tolerance(sams, wl, d):
+    w = inputs.WORKLOADS[wl].scaled(d)
+    gs = inputs.GradientStream(w, device="cuda")
+    u = gs.step(0)
+    uh = host(u)
+    hp = inputs.hash_params(w.r, seed=1)
+    o64 = Oracle("f64")
+    want = np.stack([o64.sketch(uh[i].astype(np.float64), hp, w.c) for i in range(w.n)])
+    A = abs_mass(uh, hp, w.c)
+    with sams.Context(w.d, w.n, w.r, w.c, w.k, hp) as ctx:
+        S = torch.empty((w.n, w.r, w.c), device="cuda")
+        ctx.sketch_accumulate(u, S)
+        got = host(S).astype(np.float64)
+    assert np.all(np.abs(got - want) <= TOL * A + 1e-37)
+
+
+@pytest.mark.parametrize("n,r,c", [(4, 5, 2048), (8, 5, 100_003), (16, 7, 5000), (3, 2, 17), (1, 1, 1)])
+def test_sketch_reduce_bit_exact(sams, n, r, c):
+    rng = np.random.default_rng(c)
+    S_w = (rng.standard_normal((n, r, c)) * 10.0 ** rng.uniform(-4, 2, (n, r, c))).astype(np.float32)
+    with sams.Context(1000, n, r, c, 10, inputs.hash_params(r)) as ctx:
+        Sm = torch.empty((r, c), device="cuda")
+        ctx.sketch_reduce(dev(S_w), Sm)
+        assert np.array_equal(host(Sm), Oracle("f32").sketch_mean(S_w))
+
+
+@pytest.mark.parametrize("d,n,r,c,k", SHAPES)
+@pytest.mark.parametrize("use_vhat", [True, False])
+def test_estimates_and_topk_bit_exact(sams, d, n, r, c, k, use_vhat):
+    rng = np.random.default_rng(d + r)
+    hp = inputs.hash_params(r, seed=5)
+    S = (rng.standard_normal((r, c)) * 10.0 ** rng.uniform(-3, 0, (r, c))).astype(np.float32)
+    vhat = (10.0 ** rng.uniform(-8, 0, d)).astype(np.float32) if use_vhat else None
+    o = Oracle("f32")
+    est = o.unsketch(S, vhat, d, hp)
+    idx = o.topk(est, k)
+    with sams.Context(d, n, r, c, k, hp) as ctx:
+        Sd, vd = dev(S), (dev(vhat) if use_vhat else None)
+        est_g = torch.empty(d, device="cuda")
+        ctx.unsketch_estimates(Sd, vd, est_g)
+        assert np.array_equal(host(est_g), est)
+        idx_g = torch.full((k,), -1, device="cuda", dtype=torch.int32)
+        sel_g = torch.empty(k, device="cuda")
+        ctx.unsketch_topk(Sd, vd, idx_g, sel_g)
+        assert np.array_equal(host(idx_g), idx)
+        assert np.array_equal(host(sel_g), est[idx])
+        ctx.unsketch_topk(Sd, vd, idx_g, None)                # est_sel is optional
+        assert np.array_equal(host(idx_g), idx)
+
+
+@pytest.mark.parametrize("k", [1, 100, 2_500, 19_999, 20_000])
+def test_topk_ties_go_to_the_smaller_index(sams, k):
+    # a table with three distinct magnitudes (and zeros of both signs) makes almost every |est| a tie
+    d, r, c = 20_000, 3, 64
+    rng = np.random.default_rng(k)
+    hp = inputs.hash_params(r, seed=8)
+    S = rng.choice(np.array([-2.0, -1.0, -0.0, 0.0, 1.0, 2.0], dtype=np.float32), size=(r, c))
+    o = Oracle("f32")
+    est = o.unsketch(S, None, d, hp)
+    assert len(np.unique(np.abs(est))) <= 3
+    want = o.topk(est, k)
+    with sams.Context(d, 1, r, c, k, hp) as ctx:
+        idx_g = torch.empty(k, device="cuda", dtype=torch.int32)
+        ctx.unsketch_topk(dev(S), None, idx_g, None)
+        assert np.array_equal(host(idx_g), want)
+
+
+@pytest.mark.parametrize("d,n,r,c,k", SHAPES)
+def test_gather_topk_bit_exact(sams, d, n, r, c, k):
+    rng = np.random.default_rng(d)
+    u = rng.standard_normal((n, d)).astype(np.float32)
+    vhat = (10.0 ** rng.uniform(-8, 0, d)).astype(np.float32)
+    idx = np.sort(rng.choice(d, k, replace=False)).astype(np.int32)
+    o = Oracle("f32")
+    with sams.Context(d, n, r, c, k, inputs.hash_params(r)) as ctx:
+        for vh in (vhat, None):
+            U_w, delta = o.gather(u, vh, idx)
+            Ug = torch.empty((n, k), device="cuda")
+            dg = torch.empty(k, device="cuda")
+            ctx.gather_topk(dev(u), dev(vh) if vh is not None else None, dev(idx), Ug, dg)
+            assert np.array_equal(host(Ug), U_w) and np.array_equal(host(dg), delta)
+
+
+@pytest.mark.parametrize("d,n,r,c,k", SHAPES)
+def test_amsgrad_ef_update_head_and_tail_bit_exact(sams, d, n, r, c, k):
+    rng = np.random.default_rng(d + 1)
+    o = Oracle("f32")
+    b1, b2, lr = 0.9, 0.99, 1e-3
+    f = lambda *s: (rng.standard_normal(s) * 10.0 ** rng.uniform(-4, 0, s)).astype(np.float32)
+    g1, g2, m, e, x = f(n, d), f(n, d), f(n, d), f(n, d), f(d)
+    v = (10.0 ** rng.uniform(-8, -2, d)).astype(np.float32)
+    vhat = np.maximum(v, (10.0 ** rng.uniform(-8, -2, d)).astype(np.float32))
+    idx = np.sort(rng.choice(d, k, replace=False)).astype(np.int32)
+    delta = f(k)
+    with sams.Context(d, n, r, c, k, inputs.hash_params(r)) as ctx:
+        md, ed, vd, vhd, xd = dev(m), dev(e), dev(v), dev(vhat), dev(x)
+        # first call of a run: head only, I_0 empty
+        ctx.amsgrad_ef_update(dev(g1), md, ed, vd, vhd, xd, None, None, 0, b1, b2, lr)
+        o.head(g1, m, e, v, vhat, None, b1, b2)
+        for got, want in ((md, m), (ed, e), (vd, v), (vhd, vhat), (xd, x)):
+            assert np.array_equal(host(got), want)
+        # steady state: tail of t, head of t+1 with I_t = idx, error-feedback ratio != 1
+        ctx.amsgrad_ef_update(dev(g2), md, ed, vd, vhd, xd, dev(idx), dev(delta), k, b1, b2, lr, 0.75)
+        o.tail(e, x, idx, delta, lr)
+        mask = np.zeros(d, np.uint8)
+        mask[idx] = 1
+        o.head(g2, m, e, v, vhat, mask, b1, b2, rho=0.75)
+        for got, want in ((md, m), (ed, e), (vd, v), (vhd, vhat), (xd, x)):
+            assert np.array_equal(host(got), want)
+        # last call of a run: tail only
+        idx2 = np.sort(rng.choice(d, k, replace=False)).astype(np.int32)
+        ctx.amsgrad_ef_update(None, md, ed, vd, vhd, xd, dev(idx2), dev(delta), k, b1, b2, lr)
+        o.tail(e, x, idx2, delta, lr)
+        for got, want in ((md, m), (ed, e), (vd, v), (vhd, vhat), (xd, x)):
+            assert np.array_equal(host(got), want)
+
+
+def gpu_state(b):
+    return dict(m=host(b.m).copy(), e=host(b.e_u).copy(), v=host(b.v).copy(), vhat=host(b.vhat).copy(),
+                x=host(b.x).copy())
+
+
+def near_threshold(est, k, idx_a, idx_b):
+    """Indices on which two index sets differ must have |est| within TOL of the k-th largest |est|."""
+    mag = np.abs(est.astype(np.float64))
+    tau = np.sort(mag)[-k]
+    diff = np.setxor1d(idx_a, idx_b)
+    return diff, bool(np.all(np.abs(mag[diff] - tau) <= TOL * tau))
+
+
+@pytest.mark.parametrize("wl,d,steps", [("C1", 65_536, 10), ("C2", 400_000, 6), ("C3", 300_000, 5),
+                                        ("C4", 600_000, 5), ("C5", 500_000, 3)])
+def test_chained_steps_follow_the_oracle(sams, wl, d, steps):
+    """Free-running GPU run; at every step the oracle is restarted from the GPU's previous state, so
+    each step is compared on real evolving state (bitmap of I_{t-1}, error feedback, vhat)."""
+    w = inputs.WORKLOADS[wl].scaled(d)
+    gs = inputs.GradientStream(w, device="cuda")
+    hp = inputs.hash_params(w.r, seed=w.seed)
+    o = Oracle("f32")
+    with sams.Context(w.d, w.n, w.r, w.c, w.k, hp) as ctx:
+        b = sams.Buffers(w.d, w.n, w.r, w.c, w.k, w.eps, gs.x1())
+        G = [gs.step(t) for t in range(steps)]
+        prev_mask = np.zeros(w.d, np.uint8)
+        st = dict(m=np.zeros((w.n, w.d), np.float32), e=np.zeros((w.n, w.d), np.float32),
+                  v=np.full(w.d, w.eps, np.float32), vhat=np.full(w.d, w.eps, np.float32), x=host(b.x).copy())
+        ctx.amsgrad_ef_update(G[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+        n_diff = 0
+        for t in range(steps):
+            # oracle: head of step t from the state the GPU had before its head
+            o.head(host(G[t]), st["m"], st["e"], st["v"], st["vhat"], prev_mask if t else None, w.beta1, w.beta2)
+            got = gpu_state(b)
+            for key in ("m", "e", "v", "vhat", "x"):
+                assert np.array_equal(got[key], st[key]), (t, key)
+            u = st["e"]
+            # stages 1-4 on the GPU
+            ctx.sketch_accumulate(b.e_u, b.S_workers)
+            ctx.sketch_reduce(b.S_workers, b.S_mean)
+            ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
+            ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+            S_w = host(b.S_workers)
+            want64 = np.stack([Oracle("f64").sketch(u[i].astype(np.float64), hp, w.c) for i in range(w.n)])
+            assert np.all(np.abs(S_w - want64) <= TOL * abs_mass(u, hp, w.c) + 1e-37), t
+            S_mean = host(b.S_mean)
+            assert np.array_equal(S_mean, o.sketch_mean(S_w)), t
+            est = o.unsketch(S_mean, st["vhat"], w.d, hp)         # from the GPU's table: must be bit-exact
+            idx = o.topk(est, w.k)
+            idx_g = host(b.idx)
+            assert np.array_equal(idx_g, idx), t
+            # against the oracle's own table the set may differ only at the threshold
+            S32 = o.sketch_mean(np.stack([o.sketch(u[i], hp, w.c) for i in range(w.n)]))
+            est_o = o.unsketch(S32, st["vhat"], w.d, hp)
+            diff, ok = near_threshold(est_o, w.k, o.topk(est_o, w.k), idx_g)
+            assert ok, (t, diff[:10])
+            n_diff += len(diff)
+            U_w, delta = o.gather(u, st["vhat"], idx)
+            assert np.array_equal(host(b.U_workers), U_w) and np.array_equal(host(b.delta), delta), t
+            # tail of t (+ head of t+1) on the GPU; the oracle's tail here, its head at the loop top
+            g_next = G[t + 1] if t + 1 < steps else None
+            ctx.amsgrad_ef_update(g_next, b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, w.k, w.beta1, w.beta2, w.lr)
+            o.tail(st["e"], st["x"], idx, delta, w.lr)
+            prev_mask = np.zeros(w.d, np.uint8)
+            prev_mask[idx] = 1
+        got = gpu_state(b)
+        for key in ("m", "e", "v", "vhat", "x"):
+            assert np.array_equal(got[key], st[key]), ("final", key)
+        print(f"{w.name}: {steps} steps, index-set differences vs the oracle's own tables: {n_diff}")
+
+
+def test_exact_recovery_chain_is_bit_exact_end_to_end(sams):
+    """c >= d with identity bucket hashes: one term per bucket, so even the tables are order-free and a
+    free-running GPU run must equal a free-running oracle run bit for bit."""
+    w = inputs.WORKLOADS["C4"].scaled(50_000, c=50_001, k=500, n=4)
+    gs = inputs.GradientStream(w, device="cuda")
+    hp = inputs.identity_hash_params(w.r, seed=2)
+    o = Oracle("f32")
+    st = o.init_state(host(gs.x1()), w.n, w.eps)
+    with sams.Context(w.d, w.n, w.r, w.c, w.k, hp) as ctx:
+        b = sams.Buffers(w.d, w.n, w.r, w.c, w.k, w.eps, gs.x1())
+        T = 6
+        G = [gs.step(t) for t in range(T)]
+        for t in range(T):
+            sams.run_step(ctx, b, w.beta1, w.beta2, w.lr, g_next=G[t + 1] if t + 1 < T else None,
+                          first=(t == 0), g_first=G[0])
+            out = o.step(host(G[t]), st, hp, w.c, w.k, w.beta1, w.beta2, w.lr)
+            assert np.array_equal(host(b.idx), out["idx"]), t
+            assert np.array_equal(host(b.delta), out["delta"]), t
+            assert np.array_equal(host(b.x), st["x"]), t
+        assert np.array_equal(host(b.e_u), st["e"])
+
+
+def test_invalid_arguments_are_rejected_without_launching(sams):
+    hp = inputs.hash_params(5)
+    bad = [dict(d=0), dict(k=0), dict(k=1001), dict(r=17), dict(c=0), dict(n=0), dict(d=inputs.P31)]
+    for kw in bad:
+        args = dict(d=1000, n=2, r=5, c=64, k=10)
+        args.update(kw)
+        hpp = inputs.hash_params(args["r"])
+        with pytest.raises(sams.SamsError) as ei:
+            sams.Context(args["d"], args["n"], args["r"], args["c"], args["k"], hpp)
+        assert ei.value.code == sams.SAMS_EINVAL
+    hp0 = hp.copy()
+    hp0[2, 0] = 0                                           # a = 0 is not in the family
+    with pytest.raises(sams.SamsError):
+        sams.Context(1000, 2, 5, 64, 10, hp0)
+    with sams.Context(1000, 2, 5, 64, 10, hp) as ctx:
+        u = torch.zeros((2, 1000), device="cuda")
+        S = torch.zeros((2, 5, 64), device="cuda")
+        lib = sams.load()
+        assert lib.sketch_accumulate(ctx._h, None, S.data_ptr()) == sams.SAMS_EINVAL
+        assert lib.sketch_accumulate(ctx._h, u.data_ptr() + 4, S.data_ptr()) == sams.SAMS_EINVAL   # misaligned
+        assert lib.amsgrad_ef_update(ctx._h, None, u.data_ptr(), u.data_ptr(), S.data_ptr(), S.data_ptr(),
+                                     S.data_ptr(), None, None, 5, 0.9, 0.99, 1e-3, 1.0) == sams.SAMS_EINVAL
+        assert ctx.scratch_bytes >= 4 * 1000
