@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the sketched-AMSGrad step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic gradients that are already
+resident in HBM: sketch_accumulate -> sketch_reduce -> unsketch_topk -> gather_topk ->
+amsgrad_ef_update (which finishes the iteration and runs the dense moment update of the next one).
+Prints ONE JSON line: coords/s (= d / t_step), the HBM roofline of the dominant kernel measured with
+HIP events inside the timed region, the whole-step roofline fraction, and the CPU oracle timed on a
+bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def step_algorithmic_bytes(d, n, r, c, k):
+    """Bytes the method itself must move per step: g read, m and e read+written (20nd); v read+written,
+    vhat read (12d); worker tables written once and read once, mean table written once and read once
+    ((2n+2)rc*4); sparse second round and update (k(8n+24))."""
+    return 20 * n * d + 12 * d + (2 * n + 2) * r * c * 4 + k * (8 * n + 24)
+
+
+def kernel_algorithmic_bytes(name, d, n, r, c, k):
+    """Compulsory traffic of one launch of a kernel: its inputs read once plus its outputs written once."""
+    rc4 = r * c * 4
+    table = {
+        "k_head": 20 * n * d + 12 * d,
+        "k_sketch_atomic": 4 * n * d + n * rc4,
+        "k_reduce": (n + 1) * rc4,
+        "k_estimate": rc4 + 4 * d + 4 * d,
+        "k_sel_hist": 4 * d,
+        "k_sel_count": 4 * d,
+        "k_sel_write": 4 * d + 4 * k,
+        "k_gather": k * (4 + 8 * n + 8),
+        "k_tail_x": k * 16,
+        "k_fill_u32": None,
+    }
+    return table.get(name)
+
+
+def load_traffic(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary for this
+    kernel and workload has been recorded under profiles/."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(w, sample_d):
+    """The oracle as it stands (single thread), one full step on a scaled-down copy of the workload."""
+    import numpy as np
+    from oracle import Oracle
+    from paper_2210_07454_amd import inputs
+    ws = w.scaled(sample_d)
+    gs = inputs.GradientStream(ws, device="cpu")
+    hp = inputs.hash_params(ws.r, seed=ws.seed)
+    o = Oracle("f32")
+    st = o.init_state(gs.x1().numpy(), ws.n, ws.eps)
+    o.step_c(gs.step(0).numpy(), st, hp, ws.c, ws.k, ws.beta1, ws.beta2, ws.lr)   # t = 1 (I_0 empty)
+    g = gs.step(1).numpy()
+    t0 = time.perf_counter()
+    o.step_c(g, st, hp, ws.c, ws.k, ws.beta1, ws.beta2, ws.lr)
+    dt = time.perf_counter() - t0
+    return {"value": ws.d / dt, "unit": "coords/s", "cores": 1, "kind": "oracle",
+            "sample": f"one full step (t=2) of {w.name} scaled to d={ws.d}, n={ws.n}, r={ws.r}, c={ws.c}, "
+                      f"k={ws.k}; {dt:.2f} s on 1 thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--cpu-sample-d", type=int, default=2_000_000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept resident")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the n workers are batched buffers on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2210_07454_amd import inputs, sams
+
+    w = inputs.WORKLOADS[args.workload]
+    d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
+    torch.cuda.set_device(0)
+    gs = inputs.GradientStream(w, device="cuda")
+    hp = inputs.hash_params(r, seed=w.seed)
+    ctx = sams.Context(d, n, r, c, k, hp)
+    b = sams.Buffers(d, n, r, c, k, w.eps, gs.x1())
+    pool = [gs.step(t) for t in range(max(1, args.pool))]
+    torch.cuda.synchronize()
+
+    def one_step(t):
+        ctx.sketch_accumulate(b.e_u, b.S_workers)
+        ctx.sketch_reduce(b.S_workers, b.S_mean)
+        ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
+        ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+        ctx.amsgrad_ef_update(pool[(t + 1) % len(pool)], b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, k,
+                              w.beta1, w.beta2, w.lr, 1.0)
+
+    # head of the first iteration, then warm-up
+    ctx.amsgrad_ef_update(pool[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr, 1.0)
+    t = 0
+    for _ in range(args.warmup):
+        one_step(t)
+        t += 1
+    torch.cuda.synchronize()
+
+    ctx.sams_profile_enable(True)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        one_step(t)
+        t += 1
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ctx.sams_profile_enable(False)
+    prof = ctx.sams_profile_read()
+    ms_per_step = wall * 1e3 / args.steps
+    ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
+
+    # dominant kernel: largest total device time inside the timed region
+    dom = max(prof.items(), key=lambda kv: kv[1][0])
+    dom_name, (dom_ms, dom_n) = dom
+    avg_ms = dom_ms / dom_n
+    kbytes = kernel_algorithmic_bytes(dom_name, d, n, r, c, k)
+    achieved = (kbytes / (avg_ms * 1e-3)) / 1e9 if kbytes else None
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                "traffic": load_traffic(dom_name, args.workload),
+                "algorithmic_bytes_per_launch": kbytes, "avg_launch_ms": avg_ms,
+                "launches_per_step": dom_n / args.steps}
+    step_bytes = step_algorithmic_bytes(d, n, r, c, k)
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "sketched-AMSGrad step: coords/sec and achieved HBM GB/s vs peak, 1 GPU",
+        "value": d / (ms_per_step * 1e-3),
+        "unit": "coords/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: d={d}, n={n} simulated workers, sketch {r}x{c}, k={k}, "
+                               f"{w.noise} gradients in {w.nseg} segments + {w.heavy} heavy coordinates",
+                   "d": d, "n": n, "r": r, "c": c, "k": k},
+        "worker_coords_per_s": n * d / (ms_per_step * 1e-3),
+        "device_ms_per_step": ev_ms_per_step,
+        "step_algorithmic_bytes": step_bytes,
+        "step_hbm_gbs": step_gbs,
+        "step_roofline_frac": step_gbs / HBM_PEAK_GBS,
+        "roofline": roofline,
+        "kernels_ms_per_step": {kn: round(v[0] / args.steps, 4) for kn, v in sorted(prof.items())},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_d)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

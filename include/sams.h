@@ -70,6 +70,23 @@ int64_t sams_scratch_bytes(const sams_ctx *ctx);
 int sams_last_hip_error(void);
 
 /*
+ * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the context launches is
+ * bracketed by a HIP event pair recorded on the context's stream (at most 8192 launches per window;
+ * later ones are not timed).  This measures the kernels named by sams_profile_name on the device
+ * time line; it is not part of the method and changes no result.
+ *   sams_profile_kernels   number of distinct kernels the library can launch
+ *   sams_profile_name      name of kernel `kernel` (0 <= kernel < sams_profile_kernels()), static string
+ *   sams_profile_enable    on != 0: clear the totals and start a window; on == 0: stop recording
+ *   sams_profile_read      waits for the stream, then writes, per kernel, the summed duration in
+ *                          milliseconds and the number of timed launches since the window started
+ *                          (total_ms, launches: HOST arrays of sams_profile_kernels() elements)
+ */
+int sams_profile_kernels(void);
+const char *sams_profile_name(int kernel);
+int sams_profile_enable(sams_ctx *ctx, int on);
+int sams_profile_read(sams_ctx *ctx, double *total_ms, int64_t *launches);
+
+/*
  * Writes h_j(l) and s_j(l) for every row and coordinate (the hash functions of Sec. II-C as defined
  * under sams_create), so that they can be compared one by one with another implementation.
  *   bucket  [r][d] int32, device, out     sign  [r][d] int8 (+1 / -1), device, out

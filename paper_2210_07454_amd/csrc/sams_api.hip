@@ -1,0 +1,242 @@
+// The extern "C" entry points declared in include/sams.h: argument validation, context life cycle,
+// optional per-kernel timing, and the calls into the per-stage enqueue functions.
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+
+#include "sams_ctx.h"
+
+namespace sams {
+
+int g_last_hip_error = 0;
+
+static const char *const kKernelNames[KID_COUNT] = {
+    "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
+    "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
+    "k_gather"};
+
+const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
+
+__global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t val)
+{
+    int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    int64_t st = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += st) p[i] = val;
+}
+
+__global__ void k_hash_dump(HashParams hp, int64_t d, int32_t *bucket, int8_t *sign)
+{
+    int64_t l = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (l >= d) return;
+    for (int j = 0; j < hp.r; ++j) {
+        bucket[(int64_t)j * d + l] = (int32_t)bucket_of(hp, j, (uint32_t)l);
+        sign[(int64_t)j * d + l] = sign_neg(hp, j, (uint32_t)l) ? (int8_t)-1 : (int8_t)1;
+    }
+}
+
+int enqueue_fill_u32(sams_ctx *ctx, uint32_t *p, int64_t n, uint32_t val)
+{
+    SAMS_LAUNCH(ctx, KID_FILL, k_fill_u32, grid_for(n, 256 * 4, 1 << 16), 256, p, n, val);
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+int enqueue_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign)
+{
+    SAMS_LAUNCH(ctx, KID_HASH_DUMP, k_hash_dump, grid_for(ctx->d, 256), 256, ctx->hp, ctx->d, bucket, sign);
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+// folds the finished event pairs into the per-kernel totals (synchronises the stream)
+static int prof_drain(sams_ctx *ctx)
+{
+    if (ctx->prof_used == 0) return SAMS_OK;
+    SAMS_HIP(hipStreamSynchronize(ctx->stream));
+    for (int s = 0; s < ctx->prof_used; ++s) {
+        float ms = 0.f;
+        SAMS_HIP(hipEventElapsedTime(&ms, ctx->prof[s].a, ctx->prof[s].b));
+        ctx->prof_ms[ctx->prof[s].kid] += ms;
+        ctx->prof_n[ctx->prof[s].kid] += 1;
+    }
+    ctx->prof_used = 0;
+    return SAMS_OK;
+}
+
+}  // namespace sams
+
+using namespace sams;
+
+extern "C" {
+
+int sams_last_hip_error(void) { return g_last_hip_error; }
+
+int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int64_t k,
+                const uint32_t *hash_host, void *hip_stream)
+{
+    if (!out) return SAMS_EINVAL;
+    *out = nullptr;
+    if (!hash_host) return SAMS_EINVAL;
+    if (d < 1 || d >= (int64_t)kP31 || n < 1 || n > 1024 || r < 1 || r > SAMS_MAX_ROWS || c < 1 ||
+        c >= (int64_t)kP31 || k < 1 || k > d)
+        return SAMS_EINVAL;
+    for (int j = 0; j < r; ++j) {
+        const uint32_t *h = hash_host + 4 * j;
+        if (h[0] < 1 || h[0] >= kP31 || h[1] >= kP31 || h[2] < 1 || h[2] >= kP31 || h[3] >= kP31)
+            return SAMS_EINVAL;
+    }
+    sams_ctx *ctx = new (std::nothrow) sams_ctx;
+    if (!ctx) return SAMS_ENOMEM;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->d = d; ctx->n = n; ctx->r = r; ctx->c = c; ctx->k = k;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->hp.r = r;
+    ctx->hp.modc = make_modc((uint32_t)c);
+    for (int j = 0; j < r; ++j) {
+        ctx->hp.row[j].ah = hash_host[4 * j + 0];
+        ctx->hp.row[j].bh = hash_host[4 * j + 1];
+        ctx->hp.row[j].as = hash_host[4 * j + 2];
+        ctx->hp.row[j].bs = hash_host[4 * j + 3];
+    }
+    ctx->ntile = (d + kSelTile - 1) / kSelTile;
+    const int64_t words = (d + 31) / 32;
+    struct { void **p; int64_t bytes; } allocs[] = {
+        {(void **)&ctx->est, d * 4},
+        {(void **)&ctx->bitmap, words * 4},
+        {(void **)&ctx->hist, kHistBins * 4},
+        {(void **)&ctx->sel, (int64_t)sizeof(SelState)},
+        {(void **)&ctx->cnt, 2 * ctx->ntile * 4},
+        {(void **)&ctx->base, 2 * ctx->ntile * 4},
+    };
+    for (auto &a : allocs) {
+        hipError_t e = hipMalloc(a.p, (size_t)a.bytes);
+        if (e != hipSuccess) {
+            g_last_hip_error = (int)e;
+            (void)hipGetLastError();
+            sams_destroy(ctx);
+            return SAMS_ENOMEM;
+        }
+        ctx->scratch_bytes += a.bytes;
+    }
+    int rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
+    if (rc != SAMS_OK) {
+        sams_destroy(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return SAMS_OK;
+}
+
+int sams_destroy(sams_ctx *ctx)
+{
+    if (!ctx) return SAMS_OK;
+    int rc = SAMS_OK;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; }
+    void *ptrs[] = {ctx->est, ctx->bitmap, ctx->hist, ctx->sel, ctx->cnt, ctx->base};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    if (ctx->prof) {
+        for (int s = 0; s < kProfPool; ++s) {
+            if (ctx->prof[s].a) (void)hipEventDestroy(ctx->prof[s].a);
+            if (ctx->prof[s].b) (void)hipEventDestroy(ctx->prof[s].b);
+        }
+        free(ctx->prof);
+    }
+    delete ctx;
+    return rc;
+}
+
+int64_t sams_scratch_bytes(const sams_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }
+
+int sams_profile_kernels(void) { return KID_COUNT; }
+
+const char *sams_profile_name(int kernel) { return kernel_name(kernel); }
+
+int sams_profile_enable(sams_ctx *ctx, int on)
+{
+    if (!ctx) return SAMS_EINVAL;
+    if (on) {
+        if (!ctx->prof) {
+            ctx->prof = (ProfRec *)calloc(kProfPool, sizeof(ProfRec));
+            if (!ctx->prof) return SAMS_ENOMEM;
+            for (int s = 0; s < kProfPool; ++s) {
+                SAMS_HIP(hipEventCreate(&ctx->prof[s].a));
+                SAMS_HIP(hipEventCreate(&ctx->prof[s].b));
+            }
+        }
+        SAMS_TRY(prof_drain(ctx));
+        for (int q = 0; q < KID_COUNT; ++q) { ctx->prof_ms[q] = 0.0; ctx->prof_n[q] = 0; }
+        ctx->prof_on = 1;
+    } else {
+        ctx->prof_on = 0;
+    }
+    return SAMS_OK;
+}
+
+int sams_profile_read(sams_ctx *ctx, double *total_ms, int64_t *launches)
+{
+    if (!ctx || !total_ms || !launches) return SAMS_EINVAL;
+    SAMS_TRY(prof_drain(ctx));
+    for (int q = 0; q < KID_COUNT; ++q) { total_ms[q] = ctx->prof_ms[q]; launches[q] = ctx->prof_n[q]; }
+    return SAMS_OK;
+}
+
+int sams_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign)
+{
+    if (!ctx || !bucket || !sign) return SAMS_EINVAL;
+    return enqueue_hash_dump(ctx, bucket, sign);
+}
+
+int sketch_accumulate(sams_ctx *ctx, const float *u, float *S_workers)
+{
+    if (!ctx || !u || !S_workers || !aligned16(u) || !aligned16(S_workers)) return SAMS_EINVAL;
+    return enqueue_sketch(ctx, u, S_workers);
+}
+
+int sketch_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean)
+{
+    if (!ctx || !S_workers || !S_mean || !aligned16(S_workers) || !aligned16(S_mean)) return SAMS_EINVAL;
+    return enqueue_reduce(ctx, S_workers, S_mean);
+}
+
+int unsketch_estimates(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est)
+{
+    if (!ctx || !S_mean || !est || !aligned16(S_mean) || !aligned16(est) || !aligned16(vhat))
+        return SAMS_EINVAL;
+    return enqueue_estimate(ctx, S_mean, vhat, est);
+}
+
+int unsketch_topk(sams_ctx *ctx, const float *S_mean, const float *vhat, int32_t *idx, float *est_sel)
+{
+    if (!ctx || !S_mean || !idx || !aligned16(S_mean) || !aligned16(idx) || !aligned16(vhat) ||
+        !aligned16(est_sel))
+        return SAMS_EINVAL;
+    SAMS_TRY(enqueue_estimate(ctx, S_mean, vhat, ctx->est));
+    return enqueue_select(ctx, ctx->est, idx, est_sel);
+}
+
+int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx, float *U_workers,
+                float *delta)
+{
+    if (!ctx || !u || !idx || !U_workers || !delta || !aligned16(u) || !aligned16(vhat) ||
+        !aligned16(idx) || !aligned16(U_workers) || !aligned16(delta))
+        return SAMS_EINVAL;
+    return enqueue_gather(ctx, u, vhat, idx, U_workers, delta);
+}
+
+int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, float *v, float *vhat,
+                      float *x, const int32_t *idx, const float *delta, int64_t k_sel, float beta1,
+                      float beta2, float lr, float ef_ratio)
+{
+    if (!ctx || !m || !e_u || !v || !vhat || !x) return SAMS_EINVAL;
+    if (k_sel < 0 || k_sel > ctx->k || (k_sel > 0 && (!idx || !delta))) return SAMS_EINVAL;
+    if (!aligned16(g_next) || !aligned16(m) || !aligned16(e_u) || !aligned16(v) || !aligned16(vhat) ||
+        !aligned16(x) || !aligned16(idx) || !aligned16(delta))
+        return SAMS_EINVAL;
+    SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
+    if (g_next) SAMS_TRY(enqueue_head(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
+    return SAMS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+// Internal header of the HIP library: the context, error plumbing, launch/timing helpers and the
+// declarations of the per-stage enqueue functions (one .hip file per stage group).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sams.h"
+#include "sams_hash.h"
+
+namespace sams {
+
+extern int g_last_hip_error;
+
+#define SAMS_HIP(expr)                                  \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) {                         \
+            ::sams::g_last_hip_error = (int)e_;         \
+            return SAMS_EHIP;                           \
+        }                                               \
+    } while (0)
+
+#define SAMS_TRY(expr)                                  \
+    do {                                                \
+        int rc_ = (expr);                               \
+        if (rc_ != SAMS_OK) return rc_;                 \
+    } while (0)
+
+constexpr int kWave = 64;
+constexpr int kSelTile = 2048;      // coordinates one wavefront compacts in the selection
+constexpr int kHistBins = 2048;     // first radix digit: 11 bits, then 10 and 10
+constexpr int kSelPasses = 3;
+
+// device-resident state of the radix selection (no host round trip inside a step)
+struct SelState {
+    uint32_t prefix;   // key bits decided so far (top bits of the k-th largest |est| pattern)
+    uint32_t k_rem;    // how many keys to take among those matching the prefix
+    uint32_t tau;      // final: the 31-bit pattern of the k-th largest |est|
+    uint32_t k_eq;     // final: how many coordinates with |est| == tau are selected (smallest indices)
+};
+
+// kernels, for the optional per-kernel timing (sams_profile_*)
+enum KernelId {
+    KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
+    KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
+    KID_GATHER, KID_COUNT
+};
+const char *kernel_name(int kid);
+
+constexpr int kProfPool = 8192;   // event pairs kept for one profiling window
+
+struct ProfRec {
+    hipEvent_t a, b;
+    int kid;
+};
+
+}  // namespace sams
+
+struct sams_ctx {
+    int64_t d, c, k;
+    int32_t n, r;
+    hipStream_t stream;
+    sams::HashParams hp;
+    // scratch (device)
+    float *est;              // [d]
+    uint32_t *bitmap;        // [ceil(d/32)]  bit l set <=> l in the most recent index set
+    uint32_t *hist;          // [kHistBins]
+    sams::SelState *sel;     // [1]
+    uint32_t *cnt;           // [2][ntile]  per-wavefront-tile counts: greater, equal
+    uint32_t *base;          // [2][ntile]  exclusive prefix: selected before, equal before
+    int64_t ntile;
+    int64_t scratch_bytes;
+    // per-kernel timing (host)
+    int prof_on;
+    int prof_used;
+    sams::ProfRec *prof;     // [kProfPool], events created on first enable
+    double prof_ms[sams::KID_COUNT];
+    int64_t prof_n[sams::KID_COUNT];
+};
+
+namespace sams {
+
+static inline int grid_for(int64_t work, int block, int64_t cap = (int64_t)1 << 30)
+{
+    int64_t g = (work + block - 1) / block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+static inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// Brackets one kernel launch with a HIP event pair on the context's stream while profiling is on.
+struct ProfScope {
+    sams_ctx *ctx;
+    int slot;
+    ProfScope(sams_ctx *c, int kid) : ctx(c), slot(-1)
+    {
+        if (c->prof_on && c->prof_used < kProfPool) {
+            slot = c->prof_used++;
+            c->prof[slot].kid = kid;
+            (void)hipEventRecord(c->prof[slot].a, c->stream);
+        }
+    }
+    ~ProfScope()
+    {
+        if (slot >= 0) (void)hipEventRecord(ctx->prof[slot].b, ctx->stream);
+    }
+};
+
+// SAMS_LAUNCH(ctx, KID_X, (kernel<..>), grid, block, args...)
+#define SAMS_LAUNCH(ctx, kid, kernel, grid, block, ...)                                          \
+    do {                                                                                         \
+        ::sams::ProfScope ps_((ctx), (kid));                                                     \
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, (ctx)->stream, __VA_ARGS__);      \
+    } while (0)
+
+// ---- enqueue functions (all asynchronous on ctx->stream; return SAMS_OK or SAMS_EHIP) ----
+int enqueue_fill_u32(sams_ctx *ctx, uint32_t *p, int64_t n, uint32_t val);
+int enqueue_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
+// sams_update.hip
+int enqueue_tail(sams_ctx *ctx, float *e_u, float *x, const int32_t *idx, const float *delta,
+                 int64_t k_sel, float lr, bool zero_e);
+int enqueue_head(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
+                 float beta1, float beta2, float rho);
+int enqueue_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean);
+int enqueue_gather(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx,
+                   float *U_workers, float *delta);
+// sams_sketch.hip
+int enqueue_sketch(sams_ctx *ctx, const float *u, float *S_workers);
+// sams_select.hip
+int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
+int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel);
+
+}  // namespace sams

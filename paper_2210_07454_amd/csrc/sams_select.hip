@@ -1,0 +1,269 @@
+// Stage 3 of the pipeline declared in sams.h: per-coordinate estimates (median over rows, Sec. II-C,
+// with the 1/sqrt(vhat) scaling of Alg. 3) and the exact top-k selection of Alg. 2.
+#include "sams_ctx.h"
+
+// Every formula below is evaluated as separate IEEE-754 binary32 operations, rounded to nearest:
+// no fused multiply-add is formed (here and with -ffp-contract=off on the command line), and
+// x / y and sqrtf(x) are the correctly rounded ones (hipcc's default; never build this file with
+// -ffast-math or -fno-hip-fp32-correctly-rounded-divide-sqrt).
+#pragma clang fp contract(off)
+
+namespace sams {
+// ------------------------------------------------------------------------------------------
+// stage 3a: per-coordinate estimates (Sec. II-C median, Alg. 3 scaling)
+// ------------------------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ float median_of(float (&a)[R])
+{
+    // odd-even transposition network: R rounds sort R values; compile-time unrolled
+#pragma unroll
+    for (int round = 0; round < R; ++round) {
+#pragma unroll
+        for (int p = (round & 1); p + 1 < R; p += 2) {
+            float lo = a[p + 1] < a[p] ? a[p + 1] : a[p];
+            float hi = a[p + 1] < a[p] ? a[p] : a[p + 1];
+            a[p] = lo;
+            a[p + 1] = hi;
+        }
+    }
+    return a[(R - 1) / 2];
+}
+
+template <int R>
+__global__ void __launch_bounds__(256)
+k_estimate(const float *__restrict__ S, const float *__restrict__ vhat, float *__restrict__ est,
+           HashParams hp, int64_t d, int64_t c)
+{
+    int64_t l = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (l >= d) return;
+    float a[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        uint32_t b = bucket_of(hp, j, (uint32_t)l);
+        float q = S[(int64_t)j * c + b];
+        a[j] = sign_neg(hp, j, (uint32_t)l) ? -q : q;
+    }
+    float med = median_of<R>(a);
+    est[l] = vhat ? (med / sqrtf(vhat[l])) : med;
+}
+
+// ------------------------------------------------------------------------------------------
+// stage 3b: exact top-k of |est| by radix selection on the 31-bit magnitude pattern
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t mag_key(float x) { return __float_as_uint(x) & 0x7fffffffu; }
+
+__device__ __forceinline__ int sel_shift(int pass) { return pass == 0 ? 20 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ int sel_width(int pass) { return pass == 0 ? 11 : 10; }
+
+__global__ void k_sel_init(SelState *st, uint32_t k, uint32_t *hist)
+{
+    for (int t = threadIdx.x; t < kHistBins; t += blockDim.x) hist[t] = 0;
+    if (threadIdx.x == 0) {
+        st->prefix = 0;
+        st->k_rem = k;
+        st->tau = 0;
+        st->k_eq = 0;
+    }
+}
+
+// histogram of the current digit over the keys whose higher digits equal the prefix
+__global__ void __launch_bounds__(256)
+k_sel_hist(const float *__restrict__ est, int64_t d, int pass, const SelState *__restrict__ st,
+           uint32_t *__restrict__ hist)
+{
+    __shared__ uint32_t lh[kHistBins];
+    for (int t = threadIdx.x; t < kHistBins; t += blockDim.x) lh[t] = 0;
+    __syncthreads();
+    const int shift = sel_shift(pass), width = sel_width(pass);
+    const uint32_t prefix = st->prefix;
+    const uint32_t dmask = (1u << width) - 1u;
+    int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < d; i += stride) {
+        uint32_t key = mag_key(est[i]);
+        if ((key >> (shift + width)) == prefix) atomicAdd(&lh[(key >> shift) & dmask], 1u);
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < kHistBins; t += blockDim.x)
+        if (lh[t]) atomicAdd(&hist[t], lh[t]);
+}
+
+// choose the digit in which the k_rem-th largest key lies; clear the histogram for the next pass
+__global__ void k_sel_pick(SelState *st, uint32_t *hist, int pass)
+{
+    __shared__ uint32_t lh[kHistBins];
+    const int nb = 1 << sel_width(pass);
+    for (int t = threadIdx.x; t < kHistBins; t += blockDim.x) {
+        lh[t] = hist[t];
+        hist[t] = 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t k_rem = st->k_rem, cum = 0;
+        int b = nb - 1;
+        for (; b > 0; --b) {
+            if (cum + lh[b] >= k_rem) break;
+            cum += lh[b];
+        }
+        uint32_t prefix = (st->prefix << sel_width(pass)) | (uint32_t)b;
+        st->prefix = prefix;
+        st->k_rem = k_rem - cum;
+        if (pass == kSelPasses - 1) {
+            st->tau = prefix;
+            st->k_eq = k_rem - cum;
+        }
+    }
+}
+
+// per wavefront tile of kSelTile consecutive coordinates: how many keys exceed tau, how many equal it
+__global__ void __launch_bounds__(256)
+k_sel_count(const float *__restrict__ est, int64_t d, const SelState *__restrict__ st,
+            uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq, int64_t ntile)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int64_t tile = blockIdx.x * (int64_t)(blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (tile >= ntile) return;
+    const uint32_t tau = st->tau;
+    int64_t base = tile * kSelTile;
+    uint32_t ngt = 0, neq = 0;
+    for (int s = 0; s < kSelTile; s += kWave) {
+        int64_t l = base + s + lane;
+        uint32_t key = l < d ? mag_key(est[l]) : 0u;
+        bool gt = l < d && key > tau, eq = l < d && key == tau;
+        ngt += (uint32_t)__popcll(__ballot(gt));
+        neq += (uint32_t)__popcll(__ballot(eq));
+    }
+    if (lane == 0) {
+        cnt_gt[tile] = ngt;
+        cnt_eq[tile] = neq;
+    }
+}
+
+// single block: exclusive prefixes over the tiles.  eq_base = equal keys before the tile;
+// sel_base = selected coordinates before the tile, where a tile contributes all its greater keys
+// and as many of its equal keys as are still wanted (k_eq counted from the smallest index).
+__global__ void __launch_bounds__(1024)
+k_sel_scan(const uint32_t *__restrict__ cnt_gt, const uint32_t *__restrict__ cnt_eq, int64_t ntile,
+           const SelState *__restrict__ st, uint32_t *__restrict__ sel_base,
+           uint32_t *__restrict__ eq_base)
+{
+    __shared__ uint32_t part[1024];
+    const int T = blockDim.x, t = threadIdx.x;
+    const int64_t per = (ntile + T - 1) / T;
+    const int64_t lo = (int64_t)t * per, hi = lo + per < ntile ? lo + per : ntile;
+    const uint32_t k_eq = st->k_eq;
+    // pass A: equal counts
+    uint32_t s = 0;
+    for (int64_t q = lo; q < hi; ++q) s += cnt_eq[q];
+    part[t] = s;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t run = 0;
+        for (int q = 0; q < T; ++q) { uint32_t x = part[q]; part[q] = run; run += x; }
+    }
+    __syncthreads();
+    uint32_t run = part[t];
+    __syncthreads();
+    uint32_t s2 = 0;
+    for (int64_t q = lo; q < hi; ++q) {
+        eq_base[q] = run;
+        uint32_t want = run < k_eq ? k_eq - run : 0u;
+        uint32_t ce = cnt_eq[q];
+        s2 += cnt_gt[q] + (ce < want ? ce : want);
+        run += ce;
+    }
+    // pass B: selected counts
+    part[t] = s2;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t r2 = 0;
+        for (int q = 0; q < T; ++q) { uint32_t x = part[q]; part[q] = r2; r2 += x; }
+    }
+    __syncthreads();
+    uint32_t run2 = part[t];
+    for (int64_t q = lo; q < hi; ++q) {
+        sel_base[q] = run2;
+        uint32_t eb = eq_base[q];
+        uint32_t want = eb < k_eq ? k_eq - eb : 0u;
+        uint32_t ce = cnt_eq[q];
+        run2 += cnt_gt[q] + (ce < want ? ce : want);
+    }
+}
+
+// ordered compaction: every wavefront walks its tile in index order and writes the selected
+// coordinates (key > tau, or key == tau and among the first k_eq such coordinates) at their rank
+__global__ void __launch_bounds__(256)
+k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict__ st,
+            const uint32_t *__restrict__ sel_base, const uint32_t *__restrict__ eq_base,
+            int64_t ntile, int64_t k, int32_t *__restrict__ idx, float *__restrict__ est_sel)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int64_t tile = blockIdx.x * (int64_t)(blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (tile >= ntile) return;
+    const uint32_t tau = st->tau, k_eq = st->k_eq;
+    int64_t base = tile * kSelTile;
+    uint32_t out = sel_base[tile], eqr = eq_base[tile];
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+    for (int s = 0; s < kSelTile; s += kWave) {
+        int64_t l = base + s + lane;
+        float val = l < d ? est[l] : 0.0f;
+        uint32_t key = mag_key(val);
+        bool gt = l < d && key > tau, eq = l < d && key == tau;
+        uint64_t meq = __ballot(eq);
+        bool take = gt || (eq && eqr + (uint32_t)__popcll(meq & below) < k_eq);
+        uint64_t msel = __ballot(take);
+        if (take) {
+            int64_t pos = (int64_t)out + __popcll(msel & below);
+            if (pos < k) {
+                idx[pos] = (int32_t)l;
+                if (est_sel) est_sel[pos] = val;
+            }
+        }
+        out += (uint32_t)__popcll(msel);
+        eqr += (uint32_t)__popcll(meq);
+    }
+}
+
+int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est)
+{
+    const int block = 256;
+    const int grid = grid_for(ctx->d, block);
+    switch (ctx->r) {
+#define SAMS_CASE(R)                                                                             \
+    case R:                                                                                      \
+        SAMS_LAUNCH(ctx, KID_ESTIMATE, (k_estimate<R>), grid, block, S_mean, vhat, est, ctx->hp, \
+                    ctx->d, ctx->c);                                                             \
+        break;
+        SAMS_CASE(1) SAMS_CASE(2) SAMS_CASE(3) SAMS_CASE(4) SAMS_CASE(5) SAMS_CASE(6) SAMS_CASE(7)
+        SAMS_CASE(8) SAMS_CASE(9) SAMS_CASE(10) SAMS_CASE(11) SAMS_CASE(12) SAMS_CASE(13)
+        SAMS_CASE(14) SAMS_CASE(15) SAMS_CASE(16)
+#undef SAMS_CASE
+    default:
+        return SAMS_EINVAL;
+    }
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel)
+{
+    const int64_t d = ctx->d, nt = ctx->ntile;
+    uint32_t *cnt_gt = ctx->cnt, *cnt_eq = ctx->cnt + nt;
+    uint32_t *sel_base = ctx->base, *eq_base = ctx->base + nt;
+    SAMS_LAUNCH(ctx, KID_SEL_INIT, k_sel_init, 1, 256, ctx->sel, (uint32_t)ctx->k, ctx->hist);
+    for (int pass = 0; pass < kSelPasses; ++pass) {
+        SAMS_LAUNCH(ctx, KID_SEL_HIST, k_sel_hist, grid_for(d, 256 * 16, 4096), 256, est, d, pass,
+                    ctx->sel, ctx->hist);
+        SAMS_LAUNCH(ctx, KID_SEL_PICK, k_sel_pick, 1, 256, ctx->sel, ctx->hist, pass);
+    }
+    const int waves_per_block = 256 / kWave;
+    const int tgrid = (int)((nt + waves_per_block - 1) / waves_per_block);
+    SAMS_LAUNCH(ctx, KID_SEL_COUNT, k_sel_count, tgrid, 256, est, d, ctx->sel, cnt_gt, cnt_eq, nt);
+    SAMS_LAUNCH(ctx, KID_SEL_SCAN, k_sel_scan, 1, 1024, cnt_gt, cnt_eq, nt, ctx->sel, sel_base, eq_base);
+    SAMS_LAUNCH(ctx, KID_SEL_WRITE, k_sel_write, tgrid, 256, est, d, ctx->sel, sel_base, eq_base, nt,
+                ctx->k, idx, est_sel);
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+}  // namespace sams

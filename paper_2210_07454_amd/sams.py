@@ -21,6 +21,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 
 # every symbol include/sams.h declares
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_last_hip_error", "sams_hash_dump",
+           "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk",
            "amsgrad_ef_update"]
 
@@ -52,6 +53,10 @@ def load() -> ctypes.CDLL:
     lib.sams_scratch_bytes.restype = i64
     lib.sams_last_hip_error.argtypes = []
     lib.sams_hash_dump.argtypes = [vp, vp, vp]
+    lib.sams_profile_kernels.argtypes = []
+    lib.sams_profile_name.argtypes = [ctypes.c_int]
+    lib.sams_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.sams_profile_read.argtypes = [vp, vp, vp]
     lib.sketch_accumulate.argtypes = [vp, vp, vp]
     lib.sketch_reduce.argtypes = [vp, vp, vp]
     lib.unsketch_topk.argtypes = [vp, vp, vp, vp, vp]
@@ -59,8 +64,9 @@ def load() -> ctypes.CDLL:
     lib.gather_topk.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.amsgrad_ef_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
     for name in EXPORTS:
-        if name not in ("sams_scratch_bytes",):
+        if name not in ("sams_scratch_bytes", "sams_profile_name"):
             getattr(lib, name).restype = ctypes.c_int
+    lib.sams_profile_name.restype = ctypes.c_char_p
     _lib = lib
     return lib
 
@@ -120,6 +126,17 @@ class Context:
     @property
     def scratch_bytes(self) -> int:
         return int(self._lib.sams_scratch_bytes(self._h))
+
+    def sams_profile_enable(self, on: bool):
+        _check(self._lib.sams_profile_enable(self._h, 1 if on else 0), "sams_profile_enable")
+
+    def sams_profile_read(self):
+        """{kernel name: (total milliseconds, launches)} since profiling was enabled."""
+        nk = self._lib.sams_profile_kernels()
+        ms = (ctypes.c_double * nk)()
+        cnt = (ctypes.c_int64 * nk)()
+        _check(self._lib.sams_profile_read(self._h, ms, cnt), "sams_profile_read")
+        return {self._lib.sams_profile_name(q).decode(): (ms[q], cnt[q]) for q in range(nk) if cnt[q]}
 
     # ---- entry points, same names and argument order as the C ABI ----
     def sams_hash_dump(self, bucket, sign):

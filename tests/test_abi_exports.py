@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "sams.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"^\s*(?:int|int64_t)\s+(\w+)\s*\(", text, flags=re.M)
+    return re.findall(r"^\s*(?:int|int64_t|const char \*)\s*(\w+)\s*\(", text, flags=re.M)
 
 
 def test_header_declares_the_five_stage_calls():
