@@ -53,12 +53,25 @@ typedef struct sams_ctx sams_ctx;
  *   hip_stream the hipStream_t (as void*) every later call on this context is enqueued on; NULL =
  *              the default stream.
  * Ranges: 1 <= d < 2^31-1, 1 <= n <= 1024, 1 <= r <= SAMS_MAX_ROWS, 1 <= c < 2^31-1, 1 <= k <= d.
- * Allocates the context's device scratch (about 4d bytes for the estimates, d/8 for the index bitmap,
- * plus small selection state); sams_scratch_bytes reports the total.
+ * Allocates the context's device scratch: about 4d bytes for the estimates, d/8 for the index bitmap,
+ * small selection state and, when c exceeds one LDS window, the sketch plan and its staging buffer
+ * (4*r*d bytes of plan + 4*n*r*d bytes of staging); sams_scratch_bytes reports the total.  The plan is
+ * built on the stream by this call.
  * For an even r the median of Sec. II-C is the lower middle element.
  */
 int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int64_t k,
                 const uint32_t *hash_host, void *hip_stream);
+
+/*
+ * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
+ * fp32 additions inside a bucket).  Keys:
+ *   "tile_log2"   6..15 (default 13): log2 of the coordinates per tile of the binned sketch path
+ *   "win_log2"    4..15 (default 15): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
+ *                 accumulated row by row in LDS, larger ones through the binned path
+ *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)
+ * Returns SAMS_EINVAL for an unknown key or a value out of range.
+ */
+int sams_configure(const char *key, int value);
 
 /* Waits for the context's stream, frees its scratch and the context.  NULL is a no-op. */
 int sams_destroy(sams_ctx *ctx);

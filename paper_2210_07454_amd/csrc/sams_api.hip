@@ -9,11 +9,12 @@
 namespace sams {
 
 int g_last_hip_error = 0;
+Tunables g_tun = {13, 15, 0};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
-    "k_gather"};
+    "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -119,6 +120,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
         ctx->scratch_bytes += a.bytes;
     }
     int rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
+    if (rc == SAMS_OK && g_tun.sketch_path == 0) rc = plan_create(ctx, g_tun.tile_log2, g_tun.win_log2);
     if (rc != SAMS_OK) {
         sams_destroy(ctx);
         return rc;
@@ -136,6 +138,7 @@ int sams_destroy(sams_ctx *ctx)
     void *ptrs[] = {ctx->est, ctx->bitmap, ctx->hist, ctx->sel, ctx->cnt, ctx->base};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    plan_destroy(ctx);
     if (ctx->prof) {
         for (int s = 0; s < kProfPool; ++s) {
             if (ctx->prof[s].a) (void)hipEventDestroy(ctx->prof[s].a);
@@ -145,6 +148,24 @@ int sams_destroy(sams_ctx *ctx)
     }
     delete ctx;
     return rc;
+}
+
+int sams_configure(const char *key, int value)
+{
+    if (!key) return SAMS_EINVAL;
+    if (!strcmp(key, "tile_log2")) {
+        if (value < 6 || value > 15) return SAMS_EINVAL;
+        g_tun.tile_log2 = value;
+    } else if (!strcmp(key, "win_log2")) {
+        if (value < 4 || value > 15) return SAMS_EINVAL;
+        g_tun.win_log2 = value;
+    } else if (!strcmp(key, "sketch_path")) {
+        if (value < 0 || value > 1) return SAMS_EINVAL;
+        g_tun.sketch_path = value;
+    } else {
+        return SAMS_EINVAL;
+    }
+    return SAMS_OK;
 }
 
 int64_t sams_scratch_bytes(const sams_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }

@@ -43,7 +43,7 @@ struct SelState {
 enum KernelId {
     KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
     KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
-    KID_GATHER, KID_COUNT
+    KID_GATHER, KID_PLAN_BUILD, KID_BIN_SCATTER, KID_BIN_ACCUMULATE, KID_SKETCH_LDS, KID_COUNT
 };
 const char *kernel_name(int kid);
 
@@ -53,6 +53,28 @@ struct ProfRec {
     hipEvent_t a, b;
     int kid;
 };
+
+// how sketch_accumulate is carried out for this context (chosen at creation from c and the tunables)
+enum PlanMode { PLAN_ATOMIC = 0, PLAN_LDS_ROW = 1, PLAN_BINNED = 2 };
+
+// static permutation "coordinate order -> bucket order" of the binned path (see sams_plan.hip)
+struct Plan {
+    int mode;
+    int win_log2, tile_log2;
+    int64_t nbins, ntile, dpad;
+    uint16_t *src;    // [r][dpad]  sorted position -> coordinate inside the tile (bits 0-14), sign (bit 15)
+    uint16_t *wlow;   // [r][dpad]  sorted position -> bucket inside its window
+    uint16_t *bst;    // [r][nbins+1][ntile]  first sorted position of each bin in each tile
+    float *stg;       // [n][r][dpad]  per-step staging: signed values in sorted order
+};
+
+// process-wide tunables read by sams_create (set through sams_configure)
+struct Tunables {
+    int tile_log2;     // coordinates per tile of the binned path
+    int win_log2;      // buckets per LDS window
+    int sketch_path;   // 0 = choose from c, 1 = force the global-atomic kernel
+};
+extern Tunables g_tun;
 
 }  // namespace sams
 
@@ -70,6 +92,7 @@ struct sams_ctx {
     uint32_t *base;          // [2][ntile]  exclusive prefix: selected before, equal before
     int64_t ntile;
     int64_t scratch_bytes;
+    sams::Plan plan;
     // per-kernel timing (host)
     int prof_on;
     int prof_used;
@@ -128,6 +151,10 @@ int enqueue_gather(sams_ctx *ctx, const float *u, const float *vhat, const int32
                    float *U_workers, float *delta);
 // sams_sketch.hip
 int enqueue_sketch(sams_ctx *ctx, const float *u, float *S_workers);
+// sams_plan.hip
+int plan_create(sams_ctx *ctx, int tile_log2, int win_log2);
+void plan_destroy(sams_ctx *ctx);
+int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers);
 // sams_select.hip
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
 int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel);

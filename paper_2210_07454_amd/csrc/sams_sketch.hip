@@ -31,6 +31,7 @@ k_sketch_atomic(const float *__restrict__ u, float *__restrict__ S, HashParams h
 
 int enqueue_sketch(sams_ctx *ctx, const float *u, float *S_workers)
 {
+    if (ctx->plan.mode != PLAN_ATOMIC) return enqueue_sketch_planned(ctx, u, S_workers);
     const int64_t cells = (int64_t)ctx->n * ctx->r * ctx->c;
     SAMS_TRY(enqueue_fill_u32(ctx, (uint32_t *)S_workers, cells, 0u));
     SAMS_LAUNCH(ctx, KID_SKETCH_ATOMIC, k_sketch_atomic, grid_for(ctx->d, 256), 256, u, S_workers,

@@ -21,7 +21,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 
 # every symbol include/sams.h declares
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_last_hip_error", "sams_hash_dump",
-           "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
+           "sams_configure", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk",
            "amsgrad_ef_update"]
 
@@ -53,6 +53,7 @@ def load() -> ctypes.CDLL:
     lib.sams_scratch_bytes.restype = i64
     lib.sams_last_hip_error.argtypes = []
     lib.sams_hash_dump.argtypes = [vp, vp, vp]
+    lib.sams_configure.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.sams_profile_kernels.argtypes = []
     lib.sams_profile_name.argtypes = [ctypes.c_int]
     lib.sams_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -69,6 +70,10 @@ def load() -> ctypes.CDLL:
     lib.sams_profile_name.restype = ctypes.c_char_p
     _lib = lib
     return lib
+
+
+def sams_configure(key: str, value: int):
+    _check(load().sams_configure(key.encode(), int(value)), f"sams_configure({key}={value})")
 
 
 def _ptr(t, dtype=None, shape=None, name="tensor"):

@@ -25,6 +25,24 @@ def sams():
     return mod
 
 
+PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
+    "default": dict(tile_log2=13, win_log2=15, sketch_path=0),
+    "binned-small-windows": dict(tile_log2=8, win_log2=6, sketch_path=0),
+    "binned-ragged": dict(tile_log2=10, win_log2=9, sketch_path=0),
+    "lds-row": dict(tile_log2=13, win_log2=15, sketch_path=0),
+    "global-atomic": dict(tile_log2=13, win_log2=15, sketch_path=1),
+}
+
+
+@pytest.fixture(params=list(PATHS))
+def path(request, sams):
+    for key, val in PATHS[request.param].items():
+        sams.sams_configure(key, val)
+    yield request.param
+    for key, val in PATHS["default"].items():
+        sams.sams_configure(key, val)
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -82,7 +100,7 @@ def test_hash_extreme_parameters_bit_exact(sams):
 
 
 @pytest.mark.parametrize("d,n,r,c,k", SHAPES)
-def test_sketch_accumulate_integer_inputs_bit_exact(sams, d, n, r, c, k):
+def test_sketch_accumulate_integer_inputs_bit_exact(sams, path, d, n, r, c, k):
     hp = inputs.hash_params(r, seed=3)
     amax = 64 if d * 64 < (1 << 24) else max(1, (1 << 23) // d)
     u = inputs.integer_vectors(n, d, amax=amax, seed=d).numpy()
@@ -98,7 +116,7 @@ def test_sketch_accumulate_integer_inputs_bit_exact(sams, d, n, r, c, k):
 
 
 @pytest.mark.parametrize("wl,d", [("C1", 65_536), ("C2", 300_000), ("C3", 200_000), ("C4", 500_000)])
-def test_sketch_accumulate_float_within_tolerance(sams, wl, d):
+def test_sketch_accumulate_float_within_tolerance(sams, path, wl, d):
     w = inputs.WORKLOADS[wl].scaled(d)
     gs = inputs.GradientStream(w, device="cuda")
     u = gs.step(0)
@@ -230,7 +248,7 @@ def near_threshold(est, k, idx_a, idx_b):
 
 @pytest.mark.parametrize("wl,d,steps", [("C1", 65_536, 10), ("C2", 400_000, 6), ("C3", 300_000, 5),
                                         ("C4", 600_000, 5), ("C5", 500_000, 3)])
-def test_chained_steps_follow_the_oracle(sams, wl, d, steps):
+def test_chained_steps_follow_the_oracle(sams, path, wl, d, steps):
     """Free-running GPU run; at every step the oracle is restarted from the GPU's previous state, so
     each step is compared on real evolving state (bitmap of I_{t-1}, error feedback, vhat)."""
     w = inputs.WORKLOADS[wl].scaled(d)
