@@ -34,6 +34,9 @@ def kernel_algorithmic_bytes(name, d, n, r, c, k):
     table = {
         "k_head": 20 * n * d + 12 * d,
         "k_sketch_atomic": 4 * n * d + n * rc4,
+        "k_bin_scatter": 4 * n * d,             # reads u once; the staging it writes is not algorithmic
+        "k_bin_accumulate": n * rc4,            # writes every table cell once; the staging it reads is not
+        "k_sketch_lds": 4 * n * d + n * rc4,
         "k_reduce": (n + 1) * rc4,
         "k_estimate": rc4 + 4 * d + 4 * d,
         "k_sel_hist": 4 * d,
@@ -86,6 +89,7 @@ def main():
     ap.add_argument("--cpu-sample-d", type=int, default=2_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept resident")
+    ap.add_argument("--tune", default="", help="library tunables, e.g. tile_log2=14,win_log2=15")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the n workers are batched buffers on it); "
@@ -95,6 +99,9 @@ def main():
     import torch
     from paper_2210_07454_amd import inputs, sams
 
+    for item in filter(None, args.tune.split(",")):
+        key, val = item.split("=")
+        sams.sams_configure(key, int(val))
     w = inputs.WORKLOADS[args.workload]
     d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
     torch.cuda.set_device(0)

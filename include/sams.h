@@ -66,8 +66,13 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
  *   "tile_log2"   6..15 (default 13): log2 of the coordinates per tile of the binned sketch path
- *   "win_log2"    4..15 (default 15): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
+ *   "win_log2"    4..15 (default 14): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
  *                 accumulated row by row in LDS, larger ones through the binned path
+ *   "chunk_log2"  6..11 (default 10): log2 of the stream positions the binned accumulation handles
+ *                 between two barriers
+ *   "acc_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned accumulation; must not
+ *                 exceed 2^chunk_log2, and a window plus two chunks of 8 bytes must fit in 160 KiB of LDS
+ *                 (otherwise sams_create returns SAMS_EINVAL)
  *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)
  * Returns SAMS_EINVAL for an unknown key or a value out of range.
  */
@@ -112,8 +117,11 @@ int sams_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
  *     S_workers[i][j][h_j(l)] += s_j(l) * u[i][l]      for all workers i, rows j, coordinates l.
  *   u          [n][d] in    the vectors to sketch (what amsgrad_ef_update leaves in e_u)
  *   S_workers  [n][r][c] out, overwritten (zeroed by the call, then accumulated)
- * The order in which the terms of one bucket are added is not specified (fp32 rounding may differ
- * from a sequential sum in the last bits); on inputs whose partial sums are exact the result is exact.
+ * When c exceeds one LDS window (the binned path) the terms of a bucket are added in ascending
+ * coordinate order, i.e. the result equals a sequential loop over l bit for bit and is reproducible.
+ * On the other paths (small tables accumulated with LDS atomics, or "sketch_path" = 1) the order is
+ * not specified and fp32 rounding may differ from the sequential sum in the last bits; on inputs whose
+ * partial sums are exact the result is exact on every path.
  */
 int sketch_accumulate(sams_ctx *ctx, const float *u, float *S_workers);
 

@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {13, 15, 0};
+Tunables g_tun = {13, 14, 10, 1024, 0};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -120,7 +120,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
         ctx->scratch_bytes += a.bytes;
     }
     int rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
-    if (rc == SAMS_OK && g_tun.sketch_path == 0) rc = plan_create(ctx, g_tun.tile_log2, g_tun.win_log2);
+    if (rc == SAMS_OK && g_tun.sketch_path == 0) rc = plan_create(ctx, g_tun);
     if (rc != SAMS_OK) {
         sams_destroy(ctx);
         return rc;
@@ -159,6 +159,12 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "win_log2")) {
         if (value < 4 || value > 15) return SAMS_EINVAL;
         g_tun.win_log2 = value;
+    } else if (!strcmp(key, "chunk_log2")) {
+        if (value < 6 || value > 11) return SAMS_EINVAL;
+        g_tun.chunk_log2 = value;
+    } else if (!strcmp(key, "acc_threads")) {
+        if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
+        g_tun.acc_threads = value;
     } else if (!strcmp(key, "sketch_path")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.sketch_path = value;

@@ -60,18 +60,22 @@ enum PlanMode { PLAN_ATOMIC = 0, PLAN_LDS_ROW = 1, PLAN_BINNED = 2 };
 // static permutation "coordinate order -> bucket order" of the binned path (see sams_plan.hip)
 struct Plan {
     int mode;
-    int win_log2, tile_log2;
-    int64_t nbins, ntile, dpad;
-    uint16_t *src;    // [r][dpad]  sorted position -> coordinate inside the tile (bits 0-14), sign (bit 15)
-    uint16_t *wlow;   // [r][dpad]  sorted position -> bucket inside its window
-    uint16_t *bst;    // [r][nbins+1][ntile]  first sorted position of each bin in each tile
-    float *stg;       // [n][r][dpad]  per-step staging: signed values in sorted order
+    int win_log2, tile_log2, chunk_log2, acc_threads;
+    int64_t nbins, ntile, dpad, rowlen;
+    uint16_t *src;      // [r][dpad]  sorted position in a tile -> coordinate inside the tile (bits 0-14), sign (bit 15)
+    uint16_t *bst;      // [r][ntile][nbins+1]  first sorted position of each bin's run in each tile
+    uint32_t *dst;      // [r][ntile][nbins]    start of each run in the row stream
+    uint32_t *binbase;  // [r][nbins+1]         start of each bin in the row stream (multiples of the chunk)
+    uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags
+    float *stg;         // [n][r][rowlen]       per-step staging: signed values at their stream positions
 };
 
 // process-wide tunables read by sams_create (set through sams_configure)
 struct Tunables {
     int tile_log2;     // coordinates per tile of the binned path
     int win_log2;      // buckets per LDS window
+    int chunk_log2;    // stream positions between two barriers of the accumulate kernel
+    int acc_threads;   // workgroup size of the accumulate kernel
     int sketch_path;   // 0 = choose from c, 1 = force the global-atomic kernel
 };
 extern Tunables g_tun;
@@ -152,7 +156,7 @@ int enqueue_gather(sams_ctx *ctx, const float *u, const float *vhat, const int32
 // sams_sketch.hip
 int enqueue_sketch(sams_ctx *ctx, const float *u, float *S_workers);
 // sams_plan.hip
-int plan_create(sams_ctx *ctx, int tile_log2, int win_log2);
+int plan_create(sams_ctx *ctx, const Tunables &tun);
 void plan_destroy(sams_ctx *ctx);
 int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers);
 // sams_select.hip

@@ -1,5 +1,5 @@
-// Binned Count Sketch accumulation (stage 1 of sams.h; Sec. II-C update rule) for tables that do not
-// fit in LDS.
+// Binned, order-preserving Count Sketch accumulation (stage 1 of sams.h; Sec. II-C update rule) for
+// tables that do not fit in LDS.
 //
 // The bucket hash sends consecutive coordinates to buckets spread over the whole row, so a direct
 // implementation is one uncoalesced read-modify-write per (worker, row, coordinate).  Because the
@@ -7,14 +7,23 @@
 // out once, at context creation (the plan):
 //   * coordinates are cut into tiles of L = 2^tile_log2; a row's buckets into windows ("bins") of
 //     W = 2^win_log2 buckets that fit in LDS;
-//   * inside every (row, tile) the coordinates are sorted by (bin, coordinate).  src[row][tile*L+p]
-//     names the coordinate (and its sign) that sorted position p takes, wlow[...] its bucket inside
-//     the window, and bst[row][bin][tile] the first sorted position of each bin.
+//   * every row owns a "stream": bin after bin, and inside a bin tile after tile, the coordinates that
+//     fall into that bin in ascending order.  The piece of one (tile, bin) is a "run"; runs are padded
+//     to 16 elements (one 64-byte sector) and bins to a whole number of chunks;
+//   * src[row][tile*L + p] names the coordinate (and its sign) at sorted position p of the tile,
+//     bst[row][tile][bin] the first sorted position of each run, dst[row][tile][bin] where the run
+//     starts in the row stream;
+//   * meta[row][pos] describes stream position pos: the bucket inside the window, and -- per chunk of
+//     CH consecutive positions -- a chain linking the positions that hit the same bucket.
 // Per step, pass 1 (k_bin_scatter) streams each worker's vector through LDS once and writes, for every
-// row, the signed values in sorted order (fully coalesced stores); pass 2 (k_bin_accumulate) gives one
-// workgroup per (worker, row, bin): it reads that bin's short runs from every tile (coalesced), adds
-// them into its LDS window with LDS atomics, and writes the finished window once.  No global atomics,
-// no zero-fill of the output, and every table cell is written exactly once.
+// row, the signed values to their stream positions (whole-sector stores); pass 2 (k_bin_accumulate)
+// gives one workgroup per (worker, row, bin): it reads the bin's stream chunk by chunk (contiguous) and
+// adds into its LDS window.  Inside a chunk the first position of every chain adds the whole chain, in
+// stream order, with plain loads and stores: no two threads touch the same bucket between two barriers,
+// so there are no atomics anywhere, every table cell is written exactly once, and the terms of a bucket
+// are added in ascending coordinate order -- the same order as a sequential loop over the coordinates.
+#include <stdlib.h>
+
 #include "sams_ctx.h"
 
 #pragma clang fp contract(off)
@@ -23,16 +32,21 @@ namespace sams {
 
 constexpr int kPlanThreads = 1024;
 constexpr int kScatterThreads = 256;
-constexpr int kAccThreads = 1024;
 constexpr int kNumXcd = 8;
+constexpr int kRunPad = 16;                 // run granularity in elements (64 bytes)
+
+constexpr uint32_t kMetaNextShift = 15;
+constexpr uint32_t kMetaHasNext = 1u << 26;
+constexpr uint32_t kMetaNotFirst = 1u << 27;   // padding, or a position some earlier position adds
+
+__host__ __device__ __forceinline__ int pad_run(int len) { return (len + kRunPad - 1) & ~(kRunPad - 1); }
 
 // ------------------------------------------------------------------------------------------
-// plan construction: one workgroup per (row, tile); bitonic sort of L keys in LDS
+// plan step 1: one workgroup per (row, tile); bitonic sort of the tile's coordinates by (bin, coordinate)
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kPlanThreads)
-k_plan_build(HashParams hp, int64_t d, int tile_log2, int win_log2, int64_t nbins, int64_t ntile,
-             int64_t dpad, uint16_t *__restrict__ src, uint16_t *__restrict__ wlow,
-             uint16_t *__restrict__ bst)
+k_plan_sort(HashParams hp, int64_t d, int tile_log2, int win_log2, int64_t nbins, int64_t ntile,
+            int64_t dpad, uint16_t *__restrict__ src, uint16_t *__restrict__ bst)
 {
     extern __shared__ uint32_t keys[];
     const int L = 1 << tile_log2;
@@ -65,18 +79,15 @@ k_plan_build(HashParams hp, int64_t d, int tile_log2, int win_log2, int64_t nbin
             __syncthreads();
         }
     }
-    const uint32_t lmask = (uint32_t)L - 1u, wmask = (1u << win_log2) - 1u;
+    const uint32_t lmask = (uint32_t)L - 1u;
     for (int p = threadIdx.x; p < L; p += blockDim.x) {
         uint32_t key = keys[p];
-        uint16_t s = 0, w = 0;
+        uint16_t s = 0;
         if (key != 0xffffffffu) {
             uint32_t loc = key & lmask;
-            uint32_t l = (uint32_t)(l0 + loc);
-            s = (uint16_t)(loc | (sign_neg(hp, j, l) ? 0x8000u : 0u));
-            w = (uint16_t)(bucket_of(hp, j, l) & wmask);
+            s = (uint16_t)(loc | (sign_neg(hp, j, (uint32_t)(l0 + loc)) ? 0x8000u : 0u));
         }
         src[(int64_t)j * dpad + l0 + p] = s;
-        wlow[(int64_t)j * dpad + l0 + p] = w;
     }
     // first sorted position of every bin (bin == nbins: one past the last real coordinate)
     for (int64_t b = threadIdx.x; b <= nbins; b += blockDim.x) {
@@ -85,25 +96,138 @@ k_plan_build(HashParams hp, int64_t d, int tile_log2, int win_log2, int64_t nbin
         while (lo < hi) {
             int mid = (lo + hi) >> 1;
             uint32_t key = keys[mid];
-            bool less = key != 0xffffffffu && key < want;
-            if (b == nbins) less = key != 0xffffffffu;
+            bool less = (b == nbins) ? (key != 0xffffffffu) : (key != 0xffffffffu && key < want);
             if (less) lo = mid + 1; else hi = mid;
         }
-        bst[((int64_t)j * (nbins + 1) + b) * ntile + tile] = (uint16_t)lo;
+        bst[((int64_t)j * ntile + tile) * (nbins + 1) + b] = (uint16_t)lo;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// pass 1: per tile, every worker's values into per-row sorted order
+// plan step 2: per (row, bin), exclusive prefix over the tiles of the padded run lengths
 // ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_plan_runlen(const uint16_t *__restrict__ bst, int64_t nbins, int64_t ntile, uint32_t *__restrict__ off,
+              uint32_t *__restrict__ total)
+{
+    __shared__ uint32_t part[256];
+    const int64_t bin = blockIdx.x;
+    const int j = blockIdx.y;
+    const int T = blockDim.x, t = threadIdx.x;
+    const int64_t per = (ntile + T - 1) / T;
+    const int64_t lo = (int64_t)t * per, hi = (lo + per) < ntile ? (lo + per) : ntile;
+    const uint16_t *b0 = bst + (int64_t)j * ntile * (nbins + 1) + bin;
+    uint32_t s = 0;
+    for (int64_t q = lo; q < hi; ++q) {
+        const uint16_t *e = b0 + q * (nbins + 1);
+        s += (uint32_t)pad_run((int)e[1] - (int)e[0]);
+    }
+    part[t] = s;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t run = 0;
+        for (int q = 0; q < T; ++q) { uint32_t x = part[q]; part[q] = run; run += x; }
+        total[(int64_t)j * nbins + bin] = run;
+    }
+    __syncthreads();
+    uint32_t run = part[t];
+    uint32_t *o = off + ((int64_t)j * nbins + bin) * ntile;
+    for (int64_t q = lo; q < hi; ++q) {
+        const uint16_t *e = b0 + q * (nbins + 1);
+        o[q] = run;
+        run += (uint32_t)pad_run((int)e[1] - (int)e[0]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// plan step 3: per (row, tile), where each run starts in the row stream, and the bucket of every position
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_plan_place(HashParams hp, int tile_log2, int win_log2, int64_t nbins, int64_t ntile, int64_t dpad,
+             int64_t rowlen, const uint16_t *__restrict__ src, const uint16_t *__restrict__ bst,
+             const uint32_t *__restrict__ off, const uint32_t *__restrict__ binbase,
+             uint32_t *__restrict__ dst, uint32_t *__restrict__ meta)
+{
+    const int64_t tile = blockIdx.x;
+    const int j = blockIdx.y;
+    const int64_t l0 = tile << tile_log2;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nwave = blockDim.x / kWave;
+    const uint32_t wmask = (1u << win_log2) - 1u;
+    const uint16_t *bt = bst + ((int64_t)j * ntile + tile) * (nbins + 1);
+    const uint16_t *sj = src + (int64_t)j * dpad + l0;
+    for (int64_t bin = wave; bin < nbins; bin += nwave) {
+        const int a = bt[bin], b = bt[bin + 1];
+        const uint32_t start = binbase[(int64_t)j * (nbins + 1) + bin] + off[((int64_t)j * nbins + bin) * ntile + tile];
+        if (lane == 0) dst[((int64_t)j * ntile + tile) * nbins + bin] = start;
+        for (int s = lane; s < b - a; s += kWave) {
+            uint32_t loc = sj[a + s] & 0x7fffu;
+            uint32_t wl = bucket_of(hp, j, (uint32_t)(l0 + loc)) & wmask;
+            meta[(int64_t)j * rowlen + start + s] = wl;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// plan step 4: per (row, chunk), chain the positions that share a bucket
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kPlanThreads)
+k_plan_chain(int chunk_log2, int64_t rowlen, uint32_t *__restrict__ meta)
+{
+    extern __shared__ uint32_t keys[];
+    const int CH = 1 << chunk_log2;
+    uint32_t *m = meta + (int64_t)blockIdx.y * rowlen + ((int64_t)blockIdx.x << chunk_log2);
+    for (int p = threadIdx.x; p < CH; p += blockDim.x) {
+        uint32_t w = m[p];
+        keys[p] = (w & kMetaNotFirst) ? 0xffffffffu : ((w << chunk_log2) | (uint32_t)p);
+    }
+    __syncthreads();
+    for (int k = 2; k <= CH; k <<= 1) {
+        for (int jj = k >> 1; jj > 0; jj >>= 1) {
+            for (int t = threadIdx.x; t < CH; t += blockDim.x) {
+                int other = t ^ jj;
+                if (other > t) {
+                    uint32_t a = keys[t], b = keys[other];
+                    bool up = (t & k) == 0;
+                    if ((a > b) == up) {
+                        keys[t] = b;
+                        keys[other] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const uint32_t pmask = (uint32_t)CH - 1u;
+    for (int s = threadIdx.x; s < CH; s += blockDim.x) {
+        uint32_t key = keys[s];
+        if (key == 0xffffffffu) continue;                            // padding keeps its kMetaNotFirst word
+        uint32_t wl = key >> chunk_log2, pos = key & pmask;
+        uint32_t word = wl;
+        if (s > 0 && (keys[s - 1] >> chunk_log2) == wl) word |= kMetaNotFirst;
+        if (s + 1 < CH && keys[s + 1] != 0xffffffffu && (keys[s + 1] >> chunk_log2) == wl)
+            word |= kMetaHasNext | ((keys[s + 1] & pmask) << kMetaNextShift);
+        m[pos] = word;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// pass 1: per tile, every worker's values to their positions in the row streams
+// ------------------------------------------------------------------------------------------
+// Workgroup ids are dealt round-robin to the 8 XCDs; consecutive tiles are given to the same XCD so that
+// neighbouring runs of a bin are written through one L2.
 __global__ void __launch_bounds__(kScatterThreads)
-k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ src, float *__restrict__ stg,
-              int32_t n, int32_t r, int64_t d, int tile_log2, int64_t dpad)
+k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ src, const uint16_t *__restrict__ bst,
+              const uint32_t *__restrict__ dst, float *__restrict__ stg, int32_t n, int32_t r, int64_t d,
+              int tile_log2, int64_t nbins, int64_t ntile, int64_t dpad, int64_t rowlen)
 {
     extern __shared__ float tilebuf[];
     const int L = 1 << tile_log2;
-    const int64_t l0 = (int64_t)blockIdx.x << tile_log2;
+    const int64_t per = (ntile + kNumXcd - 1) / kNumXcd;
+    const int64_t tile = (int64_t)(blockIdx.x % kNumXcd) * per + blockIdx.x / kNumXcd;
+    if (tile >= ntile || (int64_t)(blockIdx.x / kNumXcd) >= per) return;
+    const int64_t l0 = tile << tile_log2;
     const bool vec = (d & 3) == 0;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nwave = blockDim.x / kWave;
     for (int32_t i = 0; i < n; ++i) {
         const float *ui = u + (int64_t)i * d;
         if (vec) {
@@ -118,17 +242,22 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ src, flo
         __syncthreads();
         for (int32_t j = 0; j < r; ++j) {
             const uint16_t *sj = src + (int64_t)j * dpad + l0;
-            float *oj = stg + ((int64_t)i * r + j) * dpad + l0;
-            for (int p = threadIdx.x * 4; p < L; p += blockDim.x * 4) {
-                uint2 packed = *reinterpret_cast<const uint2 *>(sj + p);
-                uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
-                         s3 = packed.y >> 16;
-                float4 o;
-                o.x = tilebuf[s0 & 0x7fffu]; o.x = (s0 & 0x8000u) ? -o.x : o.x;
-                o.y = tilebuf[s1 & 0x7fffu]; o.y = (s1 & 0x8000u) ? -o.y : o.y;
-                o.z = tilebuf[s2 & 0x7fffu]; o.z = (s2 & 0x8000u) ? -o.z : o.z;
-                o.w = tilebuf[s3 & 0x7fffu]; o.w = (s3 & 0x8000u) ? -o.w : o.w;
-                *reinterpret_cast<float4 *>(oj + p) = o;
+            const uint16_t *bt = bst + ((int64_t)j * ntile + tile) * (nbins + 1);
+            const uint32_t *dt = dst + ((int64_t)j * ntile + tile) * nbins;
+            float *oj = stg + ((int64_t)i * r + j) * rowlen;
+            for (int64_t bin = wave; bin < nbins; bin += nwave) {
+                const int a = bt[bin], len = (int)bt[bin + 1] - a;
+                const int plen = pad_run(len);
+                float *o = oj + dt[bin];
+                for (int s = lane; s < plen; s += kWave) {
+                    float val = 0.f;
+                    if (s < len) {
+                        uint32_t sv = sj[a + s];
+                        val = tilebuf[sv & 0x7fffu];
+                        val = (sv & 0x8000u) ? -val : val;
+                    }
+                    o[s] = val;
+                }
             }
         }
         __syncthreads();
@@ -136,18 +265,21 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ src, flo
 }
 
 // ------------------------------------------------------------------------------------------
-// pass 2: per (worker, row, bin), add the bin's runs of every tile into an LDS window
+// pass 2: per (worker, row, bin), add the bin's stream into an LDS window, chunk by chunk
 // ------------------------------------------------------------------------------------------
-// Workgroup ids are dealt round-robin to the 8 XCDs; the mapping below places the n workers of one
-// (row, bin) on the same XCD in consecutive slots, so that the shared wlow/bst metadata is read from
-// HBM once and then served by that XCD's L2.
-__global__ void __launch_bounds__(kAccThreads)
-k_bin_accumulate(const float *__restrict__ stg, const uint16_t *__restrict__ wlow,
-                 const uint16_t *__restrict__ bst, float *__restrict__ S, int32_t n, int32_t r, int64_t c,
-                 int win_log2, int64_t nbins, int64_t ntile, int tile_log2, int64_t dpad)
+// The n workers of one (row, bin) are placed on the same XCD in consecutive slots, so that the meta
+// words they share are read from HBM once and then served by that XCD's L2.
+template <int THREADS, int UNROLL>
+__global__ void __launch_bounds__(THREADS)
+k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ meta,
+                 const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, int32_t r,
+                 int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
 {
-    extern __shared__ float win[];
+    constexpr int CH = THREADS * UNROLL;
+    extern __shared__ float lds[];
     const int W = 1 << win_log2;
+    float *win = lds;
+    uint2 *xbuf = reinterpret_cast<uint2 *>(lds + W);               // [2][CH]: (value bits, meta word)
     const int64_t id = blockIdx.x;
     const int64_t slot = id / kNumXcd;
     const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
@@ -155,53 +287,61 @@ k_bin_accumulate(const float *__restrict__ stg, const uint16_t *__restrict__ wlo
     if (group >= (int64_t)r * nbins) return;
     const int32_t j = (int32_t)(group / nbins);
     const int64_t bin = group % nbins;
-    for (int t = threadIdx.x; t < W; t += blockDim.x) win[t] = 0.f;
-    __syncthreads();
-    const uint16_t *st0 = bst + ((int64_t)j * (nbins + 1) + bin) * ntile;
-    const uint16_t *st1 = st0 + ntile;
-    const float *vbase = stg + ((int64_t)i * r + j) * dpad;
-    const uint16_t *wbase = wlow + (int64_t)j * dpad;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nwave = blockDim.x / kWave;
-    for (int64_t t0 = (int64_t)wave * kWave; t0 < ntile; t0 += (int64_t)nwave * kWave) {
-        // each lane fetches the run bounds of one tile; the wavefront then walks the 64 runs together
-        const int64_t tl = t0 + lane;
-        int a_l = 0, b_l = 0;
-        if (tl < ntile) { a_l = st0[tl]; b_l = st1[tl]; }
-        const int cnt = (ntile - t0) < kWave ? (int)(ntile - t0) : kWave;
-        for (int q = 0; q < cnt; q += 4) {
-            float v[4];
-            uint32_t w[4];
-            bool ok[4];
-            int rest = 0;
+    for (int t = threadIdx.x; t < W; t += THREADS) win[t] = 0.f;
+    const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
+    const float *v = stg + ((int64_t)i * r + j) * rowlen + b0;
+    const uint32_t *m = meta + (int64_t)j * rowlen + b0;
+    const int64_t nchunk = (b1 - b0) / CH;
+    const uint32_t wmask = (uint32_t)W - 1u;
+    float cv[UNROLL];
+    uint32_t cm[UNROLL];
+    if (nchunk > 0) {
 #pragma unroll
-            for (int z = 0; z < 4; ++z) {
-                const int a = __shfl(a_l, (q + z) & (kWave - 1)), b = __shfl(b_l, (q + z) & (kWave - 1));
-                const int pos = a + lane;
-                ok[z] = (q + z < cnt) && pos < b;
-                const int64_t off = ((t0 + q + z) << tile_log2) + pos;
-                v[z] = ok[z] ? vbase[off] : 0.f;
-                w[z] = ok[z] ? wbase[off] : 0u;
-                rest |= (q + z < cnt) && (a + kWave < b);
+        for (int z = 0; z < UNROLL; ++z) {
+            cv[z] = v[z * THREADS + threadIdx.x];
+            cm[z] = m[z * THREADS + threadIdx.x];
+        }
+    }
+    for (int64_t q = 0; q < nchunk; ++q) {
+        float nv[UNROLL];
+        uint32_t nm[UNROLL];
+        if (q + 1 < nchunk) {                                        // prefetch the next chunk
+#pragma unroll
+            for (int z = 0; z < UNROLL; ++z) {
+                nv[z] = v[(q + 1) * CH + z * THREADS + threadIdx.x];
+                nm[z] = m[(q + 1) * CH + z * THREADS + threadIdx.x];
             }
+        }
+        uint2 *xb = xbuf + (q & 1) * CH;
 #pragma unroll
-            for (int z = 0; z < 4; ++z)
-                if (ok[z]) atomicAdd(&win[w[z]], v[z]);
-            if (__any(rest)) {                                       // runs longer than one wavefront
-                for (int z = 0; z < 4 && q + z < cnt; ++z) {
-                    const int a = __shfl(a_l, q + z), b = __shfl(b_l, q + z);
-                    for (int pos = a + kWave + lane; pos < b; pos += kWave) {
-                        const int64_t off = ((t0 + q + z) << tile_log2) + pos;
-                        atomicAdd(&win[wbase[off]], vbase[off]);
-                    }
+        for (int z = 0; z < UNROLL; ++z)
+            xb[z * THREADS + threadIdx.x] = make_uint2(__float_as_uint(cv[z]), cm[z]);
+        __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+#pragma unroll
+        for (int z = 0; z < UNROLL; ++z) {
+            uint32_t word = cm[z];
+            if (!(word & kMetaNotFirst)) {
+                const uint32_t w = word & wmask;
+                float x = win[w] + cv[z];
+                while (word & kMetaHasNext) {
+                    uint2 e = xb[(word >> kMetaNextShift) & (CH - 1)];
+                    x = x + __uint_as_float(e.x);
+                    word = e.y;
                 }
+                win[w] = x;
             }
+        }
+#pragma unroll
+        for (int z = 0; z < UNROLL; ++z) {
+            cv[z] = nv[z];
+            cm[z] = nm[z];
         }
     }
     __syncthreads();
-    const int64_t b0 = bin << win_log2;
-    float *out = S + ((int64_t)i * r + j) * c + b0;
-    const int64_t lim = (c - b0) < W ? (c - b0) : W;
-    for (int t = threadIdx.x; t < lim; t += blockDim.x) out[t] = win[t];
+    const int64_t base = bin << win_log2;
+    float *out = S + ((int64_t)i * r + j) * c + base;
+    const int64_t lim = (c - base) < W ? (c - base) : W;
+    for (int t = threadIdx.x; t < lim; t += THREADS) out[t] = win[t];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -233,12 +373,58 @@ k_sketch_lds(const float *__restrict__ u, float *__restrict__ S, HashParams hp, 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-int plan_create(sams_ctx *ctx, int tile_log2, int win_log2)
+static int dev_alloc(sams_ctx *ctx, void **p, int64_t bytes)
+{
+    hipError_t e = hipMalloc(p, (size_t)(bytes > 0 ? bytes : 4));
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        return SAMS_ENOMEM;
+    }
+    ctx->scratch_bytes += bytes;
+    return SAMS_OK;
+}
+
+// (threads, unroll) variants of the accumulate kernel, selected by acc_threads / chunk_log2
+template <int TH, int UN>
+static int launch_acc(sams_ctx *ctx, float *S_workers, bool set_attr)
 {
     Plan &pl = ctx->plan;
-    pl.win_log2 = win_log2;
-    pl.tile_log2 = tile_log2;
-    const int64_t W = (int64_t)1 << win_log2, L = (int64_t)1 << tile_log2;
+    const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * TH * UN * sizeof(uint2);
+    if (set_attr) {
+        SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate<TH, UN>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        return SAMS_OK;
+    }
+    const int64_t groups = (int64_t)ctx->r * pl.nbins;
+    const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
+    ProfScope ps(ctx, KID_BIN_ACCUMULATE);
+    hipLaunchKernelGGL((k_bin_accumulate<TH, UN>), dim3((unsigned)(gpad * ctx->n)), dim3(TH), lds, ctx->stream,
+                       pl.stg, pl.meta, pl.binbase, S_workers, ctx->n, ctx->r, ctx->c, pl.win_log2, pl.nbins,
+                       pl.rowlen);
+    return SAMS_OK;
+}
+
+static int dispatch_acc(sams_ctx *ctx, float *S_workers, bool set_attr)
+{
+    const Plan &pl = ctx->plan;
+    const int un = (1 << pl.chunk_log2) / pl.acc_threads;
+#define SAMS_ACC(TH, UN) \
+    if (pl.acc_threads == TH && un == UN) return launch_acc<TH, UN>(ctx, S_workers, set_attr);
+    SAMS_ACC(1024, 1) SAMS_ACC(1024, 2) SAMS_ACC(512, 1) SAMS_ACC(512, 2) SAMS_ACC(512, 4)
+    SAMS_ACC(256, 1) SAMS_ACC(256, 2) SAMS_ACC(256, 4) SAMS_ACC(256, 8)
+#undef SAMS_ACC
+    return SAMS_EINVAL;
+}
+
+int plan_create(sams_ctx *ctx, const Tunables &tun)
+{
+    Plan &pl = ctx->plan;
+    pl.win_log2 = tun.win_log2;
+    pl.tile_log2 = tun.tile_log2;
+    pl.chunk_log2 = tun.chunk_log2;
+    pl.acc_threads = tun.acc_threads;
+    const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
     pl.mode = pl.nbins <= 1 ? PLAN_LDS_ROW : PLAN_BINNED;
     if (pl.mode == PLAN_LDS_ROW) {
@@ -246,48 +432,95 @@ int plan_create(sams_ctx *ctx, int tile_log2, int win_log2)
                                      (int)(W * 4)));
         return SAMS_OK;
     }
-    if ((pl.nbins << tile_log2) >= ((int64_t)1 << 32) - 1) return SAMS_EINVAL;   // sort key must fit 32 bits
+    // sort keys must fit 32 bits; LDS must hold a window plus the chunk exchange buffers
+    if ((pl.nbins << pl.tile_log2) >= ((int64_t)1 << 32) - 1) return SAMS_EINVAL;
+    if (pl.win_log2 + pl.chunk_log2 > 31 || pl.chunk_log2 > 11 || CH < pl.acc_threads) return SAMS_EINVAL;
+    if (W * 4 + 2 * CH * 8 > 160 * 1024) return SAMS_EINVAL;
     pl.ntile = (ctx->d + L - 1) / L;
     pl.dpad = pl.ntile * L;
-    const int64_t r = ctx->r, n = ctx->n;
-    struct { void **p; int64_t bytes; } allocs[] = {
-        {(void **)&pl.src, r * pl.dpad * 2},
-        {(void **)&pl.wlow, r * pl.dpad * 2},
-        {(void **)&pl.bst, r * (pl.nbins + 1) * pl.ntile * 2},
-        {(void **)&pl.stg, n * r * pl.dpad * 4},
-    };
-    for (auto &a : allocs) {
-        hipError_t e = hipMalloc(a.p, (size_t)a.bytes);
-        if (e != hipSuccess) {
-            g_last_hip_error = (int)e;
-            (void)hipGetLastError();
-            return SAMS_ENOMEM;
+    const int64_t r = ctx->r, n = ctx->n, NB = pl.nbins;
+    SAMS_TRY(dev_alloc(ctx, (void **)&pl.src, r * pl.dpad * 2));
+    SAMS_TRY(dev_alloc(ctx, (void **)&pl.bst, r * pl.ntile * (NB + 1) * 2));
+    SAMS_TRY(dev_alloc(ctx, (void **)&pl.dst, r * pl.ntile * NB * 4));
+    SAMS_TRY(dev_alloc(ctx, (void **)&pl.binbase, r * (NB + 1) * 4));
+    uint32_t *off = nullptr, *total = nullptr;                       // build-time only
+    if (hipMalloc((void **)&off, (size_t)(r * NB * pl.ntile * 4)) != hipSuccess ||
+        hipMalloc((void **)&total, (size_t)(r * NB * 4)) != hipSuccess) {
+        (void)hipGetLastError();
+        if (off) (void)hipFree(off);
+        return SAMS_ENOMEM;
+    }
+    int rc = SAMS_OK;
+    uint32_t *h_total = (uint32_t *)malloc((size_t)(r * NB * 4));
+    uint32_t *h_base = (uint32_t *)malloc((size_t)(r * (NB + 1) * 4));
+    do {
+        if (!h_total || !h_base) { rc = SAMS_ENOMEM; break; }
+        hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(CH * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        rc = dispatch_acc(ctx, nullptr, true);
+        if (rc != SAMS_OK) break;
+        {
+            ProfScope ps(ctx, KID_PLAN_BUILD);
+            hipLaunchKernelGGL(k_plan_sort, dim3((unsigned)pl.ntile, (unsigned)r), dim3(kPlanThreads),
+                               (size_t)(L * 4), ctx->stream, ctx->hp, ctx->d, pl.tile_log2, pl.win_log2, NB,
+                               pl.ntile, pl.dpad, pl.src, pl.bst);
+            hipLaunchKernelGGL(k_plan_runlen, dim3((unsigned)NB, (unsigned)r), dim3(256), 0, ctx->stream,
+                               pl.bst, NB, pl.ntile, off, total);
         }
-        ctx->scratch_bytes += a.bytes;
-    }
-    SAMS_HIP(hipFuncSetAttribute((const void *)k_plan_build, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)(L * 4)));
-    SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)(L * 4)));
-    SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate,
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(W * 4)));
-    {
-        ProfScope ps(ctx, KID_PLAN_BUILD);
-        hipLaunchKernelGGL(k_plan_build, dim3((unsigned)pl.ntile, (unsigned)r), dim3(kPlanThreads),
-                           (size_t)(L * 4), ctx->stream, ctx->hp, ctx->d, tile_log2, win_log2, pl.nbins,
-                           pl.ntile, pl.dpad, pl.src, pl.wlow, pl.bst);
-    }
-    SAMS_HIP(hipGetLastError());
-    return SAMS_OK;
+        e = hipMemcpyAsync(h_total, total, (size_t)(r * NB * 4), hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        int64_t rowlen = 0;
+        bool overflow = false;
+        for (int64_t j = 0; j < r; ++j) {
+            int64_t run = 0;
+            for (int64_t b = 0; b < NB; ++b) {
+                h_base[j * (NB + 1) + b] = (uint32_t)run;
+                run += ((int64_t)h_total[j * NB + b] + CH - 1) / CH * CH;
+            }
+            h_base[j * (NB + 1) + NB] = (uint32_t)run;
+            if (run >= ((int64_t)1 << 32)) overflow = true;
+            if (run > rowlen) rowlen = run;
+        }
+        if (overflow) { rc = SAMS_EINVAL; break; }
+        pl.rowlen = rowlen;
+        rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * r * rowlen * 4);
+        if (rc != SAMS_OK) break;
+        e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        rc = enqueue_fill_u32(ctx, pl.meta, r * rowlen, kMetaNotFirst);
+        if (rc != SAMS_OK) break;
+        {
+            ProfScope ps(ctx, KID_PLAN_BUILD);
+            hipLaunchKernelGGL(k_plan_place, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256), 0, ctx->stream,
+                               ctx->hp, pl.tile_log2, pl.win_log2, NB, pl.ntile, pl.dpad, rowlen, pl.src, pl.bst,
+                               off, pl.binbase, pl.dst, pl.meta);
+            hipLaunchKernelGGL(k_plan_chain, dim3((unsigned)(rowlen / CH), (unsigned)r),
+                               dim3(CH < kPlanThreads ? (unsigned)CH : kPlanThreads), (size_t)(CH * 4), ctx->stream,
+                               pl.chunk_log2, rowlen, pl.meta);
+        }
+        e = hipStreamSynchronize(ctx->stream);                       // h_base and off are released below
+        if (e == hipSuccess) e = hipGetLastError();
+        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+    } while (0);
+    free(h_total);
+    free(h_base);
+    (void)hipFree(off);
+    (void)hipFree(total);
+    return rc;
 }
 
 void plan_destroy(sams_ctx *ctx)
 {
     Plan &pl = ctx->plan;
-    void *ptrs[] = {pl.src, pl.wlow, pl.bst, pl.stg};
+    void *ptrs[] = {pl.src, pl.bst, pl.dst, pl.binbase, pl.meta, pl.stg};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
-    pl.src = pl.wlow = pl.bst = nullptr;
+    pl.src = pl.bst = nullptr;
+    pl.dst = pl.binbase = pl.meta = nullptr;
     pl.stg = nullptr;
 }
 
@@ -310,21 +543,16 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
         SAMS_HIP(hipGetLastError());
         return SAMS_OK;
     }
-    const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
+    const int64_t L = (int64_t)1 << pl.tile_log2;
     {
+        const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
         ProfScope ps(ctx, KID_BIN_SCATTER);
-        hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)pl.ntile), dim3(kScatterThreads), (size_t)(L * 4),
-                           ctx->stream, u, pl.src, pl.stg, ctx->n, ctx->r, ctx->d, pl.tile_log2, pl.dpad);
+        hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3(kScatterThreads),
+                           (size_t)(L * 4), ctx->stream, u, pl.src, pl.bst, pl.dst, pl.stg, ctx->n, ctx->r,
+                           ctx->d, pl.tile_log2, pl.nbins, pl.ntile, pl.dpad, pl.rowlen);
     }
     SAMS_HIP(hipGetLastError());
-    {
-        const int64_t groups = (int64_t)ctx->r * pl.nbins;
-        const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
-        ProfScope ps(ctx, KID_BIN_ACCUMULATE);
-        hipLaunchKernelGGL(k_bin_accumulate, dim3((unsigned)(gpad * ctx->n)), dim3(kAccThreads),
-                           (size_t)(W * 4), ctx->stream, pl.stg, pl.wlow, pl.bst, S_workers, ctx->n, ctx->r,
-                           ctx->c, pl.win_log2, pl.nbins, pl.ntile, pl.tile_log2, pl.dpad);
-    }
+    SAMS_TRY(dispatch_acc(ctx, S_workers, false));
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
 }

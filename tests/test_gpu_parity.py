@@ -26,11 +26,11 @@ def sams():
 
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
-    "default": dict(tile_log2=13, win_log2=15, sketch_path=0),
-    "binned-small-windows": dict(tile_log2=8, win_log2=6, sketch_path=0),
-    "binned-ragged": dict(tile_log2=10, win_log2=9, sketch_path=0),
-    "lds-row": dict(tile_log2=13, win_log2=15, sketch_path=0),
-    "global-atomic": dict(tile_log2=13, win_log2=15, sketch_path=1),
+    "default": dict(tile_log2=13, win_log2=14, chunk_log2=10, acc_threads=1024, sketch_path=0),
+    "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, sketch_path=0),
+    "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, sketch_path=0),
+    "binned-unroll2": dict(tile_log2=12, win_log2=8, chunk_log2=11, acc_threads=1024, sketch_path=0),
+    "global-atomic": dict(tile_log2=13, win_log2=14, chunk_log2=10, acc_threads=1024, sketch_path=1),
 }
 
 
@@ -128,8 +128,14 @@ def test_sketch_accumulate_float_within_tolerance(sams, path, wl, d):
     with sams.Context(w.d, w.n, w.r, w.c, w.k, hp) as ctx:
         S = torch.empty((w.n, w.r, w.c), device="cuda")
         ctx.sketch_accumulate(u, S)
-        got = host(S).astype(np.float64)
+        got32 = host(S)
+        got = got32.astype(np.float64)
     assert np.all(np.abs(got - want) <= TOL * A + 1e-37)
+    cfg = PATHS[path]
+    if cfg["sketch_path"] == 0 and w.c > (1 << cfg["win_log2"]):
+        # binned path: terms are added in ascending coordinate order, exactly like the oracle's loop
+        o32 = Oracle("f32")
+        assert np.array_equal(got32, np.stack([o32.sketch(uh[i], hp, w.c) for i in range(w.n)]))
 
 
 @pytest.mark.parametrize("n,r,c", [(4, 5, 2048), (8, 5, 100_003), (16, 7, 5000), (3, 2, 17), (1, 1, 1)])
