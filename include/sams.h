@@ -65,7 +65,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
 /*
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
- *   "tile_log2"   6..15 (default 13): log2 of the coordinates per tile of the binned sketch path
+ *   "tile_log2"   6..14 (default 14): log2 of the coordinates per tile of the binned sketch path
  *   "win_log2"    4..15 (default 14): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
  *                 accumulated row by row in LDS, larger ones through the binned path
  *   "chunk_log2"  6..11 (default 10): log2 of the stream positions the binned accumulation handles
@@ -73,6 +73,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "acc_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned accumulation; must not
  *                 exceed 2^chunk_log2, and a window plus two chunks of 8 bytes must fit in 160 KiB of LDS
  *                 (otherwise sams_create returns SAMS_EINVAL)
+ *   "run_pad"     16 or 32 (default 32): stream positions a (tile, window) run is padded to, so that the
+ *                 staging writes cover whole 64- or 128-byte lines
+ *   "scatter_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned scatter pass
  *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)
  * Returns SAMS_EINVAL for an unknown key or a value out of range.
  */

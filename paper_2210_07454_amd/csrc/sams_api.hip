@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {13, 14, 10, 1024, 0};
+Tunables g_tun = {14, 14, 10, 1024, 0, 1024, 32};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -154,7 +154,7 @@ int sams_configure(const char *key, int value)
 {
     if (!key) return SAMS_EINVAL;
     if (!strcmp(key, "tile_log2")) {
-        if (value < 6 || value > 15) return SAMS_EINVAL;
+        if (value < 6 || value > 14) return SAMS_EINVAL;
         g_tun.tile_log2 = value;
     } else if (!strcmp(key, "win_log2")) {
         if (value < 4 || value > 15) return SAMS_EINVAL;
@@ -165,6 +165,12 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "acc_threads")) {
         if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
         g_tun.acc_threads = value;
+    } else if (!strcmp(key, "scatter_threads")) {
+        if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
+        g_tun.scatter_threads = value;
+    } else if (!strcmp(key, "run_pad")) {
+        if (value != 16 && value != 32) return SAMS_EINVAL;
+        g_tun.run_pad = value;
     } else if (!strcmp(key, "sketch_path")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.sketch_path = value;

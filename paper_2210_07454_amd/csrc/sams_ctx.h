@@ -60,12 +60,12 @@ enum PlanMode { PLAN_ATOMIC = 0, PLAN_LDS_ROW = 1, PLAN_BINNED = 2 };
 // static permutation "coordinate order -> bucket order" of the binned path (see sams_plan.hip)
 struct Plan {
     int mode;
-    int win_log2, tile_log2, chunk_log2, acc_threads;
+    int win_log2, tile_log2, chunk_log2, acc_threads, run_pad;
     int64_t nbins, ntile, dpad, rowlen;
-    uint16_t *src;      // [r][dpad]  sorted position in a tile -> coordinate inside the tile (bits 0-14), sign (bit 15)
-    uint16_t *bst;      // [r][ntile][nbins+1]  first sorted position of each bin's run in each tile
-    uint32_t *dst;      // [r][ntile][nbins]    start of each run in the row stream
-    uint32_t *binbase;  // [r][nbins+1]         start of each bin in the row stream (multiples of the chunk)
+    uint16_t *srcp;     // [r][rowlen]      slot -> coordinate inside its tile (bits 0-14) and sign (bit 15), or padding
+    uint32_t *dst16;    // [r][rowlen/16]   stream position of each group of 16 slots
+    uint32_t *pbase;    // [r][ntile+1]     first slot of each tile
+    uint32_t *binbase;  // [r][nbins+1]     start of each bin in the row stream (multiples of the chunk)
     uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags
     float *stg;         // [n][r][rowlen]       per-step staging: signed values at their stream positions
 };
@@ -77,6 +77,8 @@ struct Tunables {
     int chunk_log2;    // stream positions between two barriers of the accumulate kernel
     int acc_threads;   // workgroup size of the accumulate kernel
     int sketch_path;   // 0 = choose from c, 1 = force the global-atomic kernel
+    int scatter_threads;  // workgroup size of the scatter kernel
+    int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
 };
 extern Tunables g_tun;
 

@@ -10,9 +10,9 @@
 //   * every row owns a "stream": bin after bin, and inside a bin tile after tile, the coordinates that
 //     fall into that bin in ascending order.  The piece of one (tile, bin) is a "run"; runs are padded
 //     to 16 elements (one 64-byte sector) and bins to a whole number of chunks;
-//   * src[row][tile*L + p] names the coordinate (and its sign) at sorted position p of the tile,
-//     bst[row][tile][bin] the first sorted position of each run, dst[row][tile][bin] where the run
-//     starts in the row stream;
+//   * seen from a tile, its padded runs laid one after the other are its "slots": srcp[row][slot]
+//     names the coordinate (and its sign) a slot takes its value from (or marks padding), and
+//     dst16[row][slot / 16] says where in the row stream that group of 16 slots goes;
 //   * meta[row][pos] describes stream position pos: the bucket inside the window, and -- per chunk of
 //     CH consecutive positions -- a chain linking the positions that hit the same bucket.
 // Per step, pass 1 (k_bin_scatter) streams each worker's vector through LDS once and writes, for every
@@ -33,13 +33,14 @@ namespace sams {
 constexpr int kPlanThreads = 1024;
 constexpr int kScatterThreads = 256;
 constexpr int kNumXcd = 8;
-constexpr int kRunPad = 16;                 // run granularity in elements (64 bytes)
+constexpr int kRunPad = 16;                 // slot-group granularity in elements (64 bytes); runs are padded to a multiple of it
 
+constexpr uint16_t kSrcPad = 0x7fffu;          // slot source meaning "padding": tiles hold at most 2^14 coordinates
 constexpr uint32_t kMetaNextShift = 15;
 constexpr uint32_t kMetaHasNext = 1u << 26;
 constexpr uint32_t kMetaNotFirst = 1u << 27;   // padding, or a position some earlier position adds
 
-__host__ __device__ __forceinline__ int pad_run(int len) { return (len + kRunPad - 1) & ~(kRunPad - 1); }
+__host__ __device__ __forceinline__ int pad_run(int len, int pad) { return (len + pad - 1) & ~(pad - 1); }
 
 // ------------------------------------------------------------------------------------------
 // plan step 1: one workgroup per (row, tile); bitonic sort of the tile's coordinates by (bin, coordinate)
@@ -107,7 +108,7 @@ k_plan_sort(HashParams hp, int64_t d, int tile_log2, int win_log2, int64_t nbins
 // plan step 2: per (row, bin), exclusive prefix over the tiles of the padded run lengths
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_plan_runlen(const uint16_t *__restrict__ bst, int64_t nbins, int64_t ntile, uint32_t *__restrict__ off,
+k_plan_runlen(const uint16_t *__restrict__ bst, int pad, int64_t nbins, int64_t ntile, uint32_t *__restrict__ off,
               uint32_t *__restrict__ total)
 {
     __shared__ uint32_t part[256];
@@ -120,7 +121,7 @@ k_plan_runlen(const uint16_t *__restrict__ bst, int64_t nbins, int64_t ntile, ui
     uint32_t s = 0;
     for (int64_t q = lo; q < hi; ++q) {
         const uint16_t *e = b0 + q * (nbins + 1);
-        s += (uint32_t)pad_run((int)e[1] - (int)e[0]);
+        s += (uint32_t)pad_run((int)e[1] - (int)e[0], pad);
     }
     part[t] = s;
     __syncthreads();
@@ -135,19 +136,44 @@ k_plan_runlen(const uint16_t *__restrict__ bst, int64_t nbins, int64_t ntile, ui
     for (int64_t q = lo; q < hi; ++q) {
         const uint16_t *e = b0 + q * (nbins + 1);
         o[q] = run;
-        run += (uint32_t)pad_run((int)e[1] - (int)e[0]);
+        run += (uint32_t)pad_run((int)e[1] - (int)e[0], pad);
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// plan step 3: per (row, tile), where each run starts in the row stream, and the bucket of every position
+// plan step 3a: per (row, tile), the padded length of the tile's slots
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_plan_place(HashParams hp, int tile_log2, int win_log2, int64_t nbins, int64_t ntile, int64_t dpad,
+k_plan_tilelen(const uint16_t *__restrict__ bst, int pad, int64_t nbins, int64_t ntile, uint32_t *__restrict__ tilelen)
+{
+    __shared__ uint32_t part[256];
+    const int64_t tile = blockIdx.x;
+    const int j = blockIdx.y;
+    const uint16_t *bt = bst + ((int64_t)j * ntile + tile) * (nbins + 1);
+    uint32_t s = 0;
+    for (int64_t b = threadIdx.x; b < nbins; b += blockDim.x) s += (uint32_t)pad_run((int)bt[b + 1] - (int)bt[b], pad);
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+        if ((int)threadIdx.x < h) part[threadIdx.x] += part[threadIdx.x + h];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) tilelen[(int64_t)j * ntile + tile] = part[0];
+}
+
+// ------------------------------------------------------------------------------------------
+// plan step 3b: per (row, tile): the source of every slot, the stream position of every group of 16
+// slots, and the bucket of every stream position
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_plan_place(HashParams hp, int pad, int tile_log2, int win_log2, int64_t nbins, int64_t ntile, int64_t dpad,
              int64_t rowlen, const uint16_t *__restrict__ src, const uint16_t *__restrict__ bst,
              const uint32_t *__restrict__ off, const uint32_t *__restrict__ binbase,
-             uint32_t *__restrict__ dst, uint32_t *__restrict__ meta)
+             const uint32_t *__restrict__ pbase, uint16_t *__restrict__ srcp, uint32_t *__restrict__ dst16,
+             uint32_t *__restrict__ meta)
 {
+    extern __shared__ uint32_t pst[];                               // [nbins + 1] padded prefix inside the tile
+    __shared__ uint32_t part[256];
     const int64_t tile = blockIdx.x;
     const int j = blockIdx.y;
     const int64_t l0 = tile << tile_log2;
@@ -155,14 +181,39 @@ k_plan_place(HashParams hp, int tile_log2, int win_log2, int64_t nbins, int64_t 
     const uint32_t wmask = (1u << win_log2) - 1u;
     const uint16_t *bt = bst + ((int64_t)j * ntile + tile) * (nbins + 1);
     const uint16_t *sj = src + (int64_t)j * dpad + l0;
+    // exclusive prefix of the padded run lengths over the bins (blocked two-level scan)
+    const int T = blockDim.x, t = threadIdx.x;
+    const int64_t per = (nbins + T - 1) / T;
+    const int64_t lo = (int64_t)t * per, hi = (lo + per) < nbins ? (lo + per) : nbins;
+    uint32_t sum = 0;
+    for (int64_t b = lo; b < hi; ++b) sum += (uint32_t)pad_run((int)bt[b + 1] - (int)bt[b], pad);
+    part[t] = sum;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t run = 0;
+        for (int q = 0; q < T; ++q) { uint32_t x = part[q]; part[q] = run; run += x; }
+    }
+    __syncthreads();
+    uint32_t run = part[t];
+    for (int64_t b = lo; b < hi; ++b) {
+        pst[b] = run;
+        run += (uint32_t)pad_run((int)bt[b + 1] - (int)bt[b], pad);
+    }
+    __syncthreads();
+    const uint32_t p0 = pbase[(int64_t)j * (ntile + 1) + tile];
     for (int64_t bin = wave; bin < nbins; bin += nwave) {
-        const int a = bt[bin], b = bt[bin + 1];
+        const int a = bt[bin], len = (int)bt[bin + 1] - a, plen = pad_run(len, pad);
         const uint32_t start = binbase[(int64_t)j * (nbins + 1) + bin] + off[((int64_t)j * nbins + bin) * ntile + tile];
-        if (lane == 0) dst[((int64_t)j * ntile + tile) * nbins + bin] = start;
-        for (int s = lane; s < b - a; s += kWave) {
-            uint32_t loc = sj[a + s] & 0x7fffu;
-            uint32_t wl = bucket_of(hp, j, (uint32_t)(l0 + loc)) & wmask;
-            meta[(int64_t)j * rowlen + start + s] = wl;
+        const uint32_t po = p0 + pst[bin];
+        for (int s = lane; s < plen; s += kWave) {
+            uint16_t sv = kSrcPad;
+            if (s < len) {
+                sv = sj[a + s];
+                uint32_t wl = bucket_of(hp, j, (uint32_t)(l0 + (sv & 0x7fffu))) & wmask;
+                meta[(int64_t)j * rowlen + start + s] = wl;
+            }
+            srcp[(int64_t)j * rowlen + po + s] = sv;
+            if ((s & (kRunPad - 1)) == 0) dst16[((int64_t)j * rowlen + po + s) / kRunPad] = start + (uint32_t)s;
         }
     }
 }
@@ -214,20 +265,21 @@ k_plan_chain(int chunk_log2, int64_t rowlen, uint32_t *__restrict__ meta)
 // pass 1: per tile, every worker's values to their positions in the row streams
 // ------------------------------------------------------------------------------------------
 // Workgroup ids are dealt round-robin to the 8 XCDs; consecutive tiles are given to the same XCD so that
-// neighbouring runs of a bin are written through one L2.
-__global__ void __launch_bounds__(kScatterThreads)
-k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ src, const uint16_t *__restrict__ bst,
-              const uint32_t *__restrict__ dst, float *__restrict__ stg, int32_t n, int32_t r, int64_t d,
-              int tile_log2, int64_t nbins, int64_t ntile, int64_t dpad, int64_t rowlen)
+// neighbouring runs of a bin are written through one L2.  A thread owns 4 consecutive slots (always inside
+// one group of 16, hence one run): one 8-byte load of their sources, one 4-byte load of the group's
+// stream position, 4 LDS reads and one 16-byte store -- nothing depends on another global load.
+__global__ void __launch_bounds__(1024)
+k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
+              const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, int32_t r, int64_t d,
+              int tile_log2, int64_t ntile, int64_t rowlen)
 {
     extern __shared__ float tilebuf[];
     const int L = 1 << tile_log2;
     const int64_t per = (ntile + kNumXcd - 1) / kNumXcd;
     const int64_t tile = (int64_t)(blockIdx.x % kNumXcd) * per + blockIdx.x / kNumXcd;
-    if (tile >= ntile || (int64_t)(blockIdx.x / kNumXcd) >= per) return;
+    if (tile >= ntile) return;
     const int64_t l0 = tile << tile_log2;
     const bool vec = (d & 3) == 0;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nwave = blockDim.x / kWave;
     for (int32_t i = 0; i < n; ++i) {
         const float *ui = u + (int64_t)i * d;
         if (vec) {
@@ -241,23 +293,21 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ src, con
         }
         __syncthreads();
         for (int32_t j = 0; j < r; ++j) {
-            const uint16_t *sj = src + (int64_t)j * dpad + l0;
-            const uint16_t *bt = bst + ((int64_t)j * ntile + tile) * (nbins + 1);
-            const uint32_t *dt = dst + ((int64_t)j * ntile + tile) * nbins;
+            const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
+            const uint16_t *sj = srcp + (int64_t)j * rowlen;
+            const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
             float *oj = stg + ((int64_t)i * r + j) * rowlen;
-            for (int64_t bin = wave; bin < nbins; bin += nwave) {
-                const int a = bt[bin], len = (int)bt[bin + 1] - a;
-                const int plen = pad_run(len);
-                float *o = oj + dt[bin];
-                for (int s = lane; s < plen; s += kWave) {
-                    float val = 0.f;
-                    if (s < len) {
-                        uint32_t sv = sj[a + s];
-                        val = tilebuf[sv & 0x7fffu];
-                        val = (sv & 0x8000u) ? -val : val;
-                    }
-                    o[s] = val;
-                }
+            for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
+                const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
+                const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+                const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
+                               s3 = packed.y >> 16;
+                float4 v;
+                v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
+                v.y = (s1 == kSrcPad) ? 0.f : tilebuf[s1 & 0x7fffu]; v.y = (s1 & 0x8000u) ? -v.y : v.y;
+                v.z = (s2 == kSrcPad) ? 0.f : tilebuf[s2 & 0x7fffu]; v.z = (s2 & 0x8000u) ? -v.z : v.z;
+                v.w = (s3 == kSrcPad) ? 0.f : tilebuf[s3 & 0x7fffu]; v.w = (s3 & 0x8000u) ? -v.w : v.w;
+                *reinterpret_cast<float4 *>(oj + at) = v;
             }
         }
         __syncthreads();
@@ -424,6 +474,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.tile_log2 = tun.tile_log2;
     pl.chunk_log2 = tun.chunk_log2;
     pl.acc_threads = tun.acc_threads;
+    pl.run_pad = tun.run_pad;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
     pl.mode = pl.nbins <= 1 ? PLAN_LDS_ROW : PLAN_BINNED;
@@ -439,25 +490,28 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.ntile = (ctx->d + L - 1) / L;
     pl.dpad = pl.ntile * L;
     const int64_t r = ctx->r, n = ctx->n, NB = pl.nbins;
-    SAMS_TRY(dev_alloc(ctx, (void **)&pl.src, r * pl.dpad * 2));
-    SAMS_TRY(dev_alloc(ctx, (void **)&pl.bst, r * pl.ntile * (NB + 1) * 2));
-    SAMS_TRY(dev_alloc(ctx, (void **)&pl.dst, r * pl.ntile * NB * 4));
+    if (pl.tile_log2 > 14 || NB > 8192) return SAMS_EINVAL;          // kSrcPad; LDS prefix in k_plan_place
     SAMS_TRY(dev_alloc(ctx, (void **)&pl.binbase, r * (NB + 1) * 4));
-    uint32_t *off = nullptr, *total = nullptr;                       // build-time only
-    if (hipMalloc((void **)&off, (size_t)(r * NB * pl.ntile * 4)) != hipSuccess ||
-        hipMalloc((void **)&total, (size_t)(r * NB * 4)) != hipSuccess) {
-        (void)hipGetLastError();
-        if (off) (void)hipFree(off);
-        return SAMS_ENOMEM;
-    }
+    SAMS_TRY(dev_alloc(ctx, (void **)&pl.pbase, r * (pl.ntile + 1) * 4));
+    // build-time only: tile-sorted sources, run starts, per-(bin, tile) offsets, totals, tile lengths
+    uint16_t *src = nullptr, *bst = nullptr;
+    uint32_t *off = nullptr, *total = nullptr, *tilelen = nullptr;
+    void **tmp[] = {(void **)&src, (void **)&bst, (void **)&off, (void **)&total, (void **)&tilelen};
+    const int64_t tmpbytes[] = {r * pl.dpad * 2, r * pl.ntile * (NB + 1) * 2, r * NB * pl.ntile * 4, r * NB * 4,
+                                r * pl.ntile * 4};
     int rc = SAMS_OK;
+    for (int q = 0; q < 5 && rc == SAMS_OK; ++q)
+        if (hipMalloc(tmp[q], (size_t)tmpbytes[q]) != hipSuccess) { (void)hipGetLastError(); rc = SAMS_ENOMEM; }
     uint32_t *h_total = (uint32_t *)malloc((size_t)(r * NB * 4));
     uint32_t *h_base = (uint32_t *)malloc((size_t)(r * (NB + 1) * 4));
+    uint32_t *h_tile = (uint32_t *)malloc((size_t)(r * (pl.ntile + 1) * 4));
     do {
-        if (!h_total || !h_base) { rc = SAMS_ENOMEM; break; }
+        if (rc != SAMS_OK) break;
+        if (!h_total || !h_base || !h_tile) { rc = SAMS_ENOMEM; break; }
         hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(CH * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((NB + 1) * 4));
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         rc = dispatch_acc(ctx, nullptr, true);
         if (rc != SAMS_OK) break;
@@ -465,11 +519,15 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
             ProfScope ps(ctx, KID_PLAN_BUILD);
             hipLaunchKernelGGL(k_plan_sort, dim3((unsigned)pl.ntile, (unsigned)r), dim3(kPlanThreads),
                                (size_t)(L * 4), ctx->stream, ctx->hp, ctx->d, pl.tile_log2, pl.win_log2, NB,
-                               pl.ntile, pl.dpad, pl.src, pl.bst);
+                               pl.ntile, pl.dpad, src, bst);
             hipLaunchKernelGGL(k_plan_runlen, dim3((unsigned)NB, (unsigned)r), dim3(256), 0, ctx->stream,
-                               pl.bst, NB, pl.ntile, off, total);
+                               bst, pl.run_pad, NB, pl.ntile, off, total);
+            hipLaunchKernelGGL(k_plan_tilelen, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256), 0, ctx->stream,
+                               bst, pl.run_pad, NB, pl.ntile, tilelen);
         }
         e = hipMemcpyAsync(h_total, total, (size_t)(r * NB * 4), hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(h_tile, tilelen, (size_t)(r * pl.ntile * 4), hipMemcpyDeviceToHost, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         int64_t rowlen = 0;
@@ -486,18 +544,34 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         }
         if (overflow) { rc = SAMS_EINVAL; break; }
         pl.rowlen = rowlen;
-        rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
+        // exclusive prefix of the tile lengths, in place, back to front so that nothing is overwritten early
+        for (int64_t j = r - 1; j >= 0; --j) {
+            uint32_t run = 0;
+            uint32_t *row = (uint32_t *)malloc((size_t)((pl.ntile + 1) * 4));
+            if (!row) { rc = SAMS_ENOMEM; break; }
+            for (int64_t q = 0; q < pl.ntile; ++q) { row[q] = run; run += h_tile[j * pl.ntile + q]; }
+            row[pl.ntile] = run;
+            for (int64_t q = 0; q <= pl.ntile; ++q) h_tile[j * (pl.ntile + 1) + q] = row[q];
+            free(row);
+        }
+        if (rc != SAMS_OK) break;
+        rc = dev_alloc(ctx, (void **)&pl.srcp, r * rowlen * 2);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen / kRunPad) * 4);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * r * rowlen * 4);
         if (rc != SAMS_OK) break;
         e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(pl.pbase, h_tile, (size_t)(r * (pl.ntile + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         rc = enqueue_fill_u32(ctx, pl.meta, r * rowlen, kMetaNotFirst);
         if (rc != SAMS_OK) break;
         {
             ProfScope ps(ctx, KID_PLAN_BUILD);
-            hipLaunchKernelGGL(k_plan_place, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256), 0, ctx->stream,
-                               ctx->hp, pl.tile_log2, pl.win_log2, NB, pl.ntile, pl.dpad, rowlen, pl.src, pl.bst,
-                               off, pl.binbase, pl.dst, pl.meta);
+            hipLaunchKernelGGL(k_plan_place, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256),
+                               (size_t)((NB + 1) * 4), ctx->stream, ctx->hp, pl.run_pad, pl.tile_log2, pl.win_log2, NB,
+                               pl.ntile, pl.dpad, rowlen, src, bst, off, pl.binbase, pl.pbase, pl.srcp, pl.dst16,
+                               pl.meta);
             hipLaunchKernelGGL(k_plan_chain, dim3((unsigned)(rowlen / CH), (unsigned)r),
                                dim3(CH < kPlanThreads ? (unsigned)CH : kPlanThreads), (size_t)(CH * 4), ctx->stream,
                                pl.chunk_log2, rowlen, pl.meta);
@@ -508,19 +582,20 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     } while (0);
     free(h_total);
     free(h_base);
-    (void)hipFree(off);
-    (void)hipFree(total);
+    free(h_tile);
+    for (int q = 0; q < 5; ++q)
+        if (*tmp[q]) (void)hipFree(*tmp[q]);
     return rc;
 }
 
 void plan_destroy(sams_ctx *ctx)
 {
     Plan &pl = ctx->plan;
-    void *ptrs[] = {pl.src, pl.bst, pl.dst, pl.binbase, pl.meta, pl.stg};
+    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.stg};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
-    pl.src = pl.bst = nullptr;
-    pl.dst = pl.binbase = pl.meta = nullptr;
+    pl.srcp = nullptr;
+    pl.dst16 = pl.pbase = pl.binbase = pl.meta = nullptr;
     pl.stg = nullptr;
 }
 
@@ -547,9 +622,9 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
     {
         const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
         ProfScope ps(ctx, KID_BIN_SCATTER);
-        hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3(kScatterThreads),
-                           (size_t)(L * 4), ctx->stream, u, pl.src, pl.bst, pl.dst, pl.stg, ctx->n, ctx->r,
-                           ctx->d, pl.tile_log2, pl.nbins, pl.ntile, pl.dpad, pl.rowlen);
+        hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3((unsigned)g_tun.scatter_threads),
+                           (size_t)(L * 4), ctx->stream, u, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, ctx->r,
+                           ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);
     }
     SAMS_HIP(hipGetLastError());
     SAMS_TRY(dispatch_acc(ctx, S_workers, false));

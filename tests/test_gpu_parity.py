@@ -26,11 +26,16 @@ def sams():
 
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
-    "default": dict(tile_log2=13, win_log2=14, chunk_log2=10, acc_threads=1024, sketch_path=0),
-    "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, sketch_path=0),
-    "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, sketch_path=0),
-    "binned-unroll2": dict(tile_log2=12, win_log2=8, chunk_log2=11, acc_threads=1024, sketch_path=0),
-    "global-atomic": dict(tile_log2=13, win_log2=14, chunk_log2=10, acc_threads=1024, sketch_path=1),
+    "default": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32, scatter_threads=1024,
+                    sketch_path=0),
+    "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=16,
+                                 scatter_threads=256, sketch_path=0),
+    "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, run_pad=32,
+                          scatter_threads=512, sketch_path=0),
+    "binned-unroll2": dict(tile_log2=12, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=16,
+                           scatter_threads=1024, sketch_path=0),
+    "global-atomic": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
+                          scatter_threads=1024, sketch_path=1),
 }
 
 
