@@ -76,6 +76,8 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "run_pad"     16 or 32 (default 32): stream positions a (tile, window) run is padded to, so that the
  *                 staging writes cover whole 64- or 128-byte lines
  *   "scatter_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned scatter pass
+ *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
+ *                 1: one gather per (row, coordinate) straight from the table
  *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)
  * Returns SAMS_EINVAL for an unknown key or a value out of range.
  */

@@ -9,12 +9,13 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {14, 14, 10, 1024, 0, 1024, 32};
+Tunables g_tun = {14, 14, 10, 1024, 0, 1024, 0, 32};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
-    "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds"};
+    "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds", "k_bin_lookup",
+    "k_bin_collect", "k_est_median"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -168,6 +169,9 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "scatter_threads")) {
         if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
         g_tun.scatter_threads = value;
+    } else if (!strcmp(key, "estimate_path")) {
+        if (value < 0 || value > 1) return SAMS_EINVAL;
+        g_tun.estimate_path = value;
     } else if (!strcmp(key, "run_pad")) {
         if (value != 16 && value != 32) return SAMS_EINVAL;
         g_tun.run_pad = value;

@@ -395,6 +395,97 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
 }
 
 // ------------------------------------------------------------------------------------------
+// the plan run backwards, for the recovery of stage 3 (Sec. II-C: the row estimates s_j(l) S[j,h_j(l)])
+// ------------------------------------------------------------------------------------------
+// Reading S[j][h_j(l)] for every coordinate is the same permutation as the sketch, in the other
+// direction: k_bin_lookup gives one workgroup per (row, bin), which holds the bin's window of the mean
+// table in LDS and writes the looked-up value of every stream position (contiguous); k_bin_collect
+// gives one workgroup per tile, which brings the values of its slots back into coordinate order through
+// LDS, applies the signs, and writes rowest[row][l] = s_row(l) * S[row][h_row(l)] (contiguous).
+__global__ void __launch_bounds__(1024)
+k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta,
+             const uint32_t *__restrict__ binbase, float *__restrict__ lk, int64_t c, int win_log2,
+             int64_t nbins, int64_t rowlen)
+{
+    extern __shared__ float win[];
+    const int W = 1 << win_log2;
+    const int64_t bin = blockIdx.x;
+    const int j = blockIdx.y;
+    const int64_t base = bin << win_log2;
+    const float *Sj = S_mean + (int64_t)j * c + base;
+    const int64_t lim = (c - base) < W ? (c - base) : W;
+    for (int t = threadIdx.x; t < W; t += blockDim.x) win[t] = t < lim ? Sj[t] : 0.f;
+    __syncthreads();
+    const uint32_t wmask = (uint32_t)W - 1u;
+    const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
+    const uint4 *m4 = reinterpret_cast<const uint4 *>(meta + (int64_t)j * rowlen + b0);
+    float4 *o4 = reinterpret_cast<float4 *>(lk + (int64_t)j * rowlen + b0);
+    const int64_t n4 = (b1 - b0) >> 2;                               // bins are whole chunks: a multiple of 4
+    for (int64_t q = threadIdx.x; q < n4; q += blockDim.x) {
+        const uint4 w = m4[q];
+        o4[q] = make_float4(win[w.x & wmask], win[w.y & wmask], win[w.z & wmask], win[w.w & wmask]);
+    }
+}
+
+__global__ void __launch_bounds__(1024)
+k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
+              const uint32_t *__restrict__ pbase, float *__restrict__ rowest, int32_t r, int64_t d,
+              int tile_log2, int64_t ntile, int64_t rowlen)
+{
+    extern __shared__ float rowbuf[];                                // [2][L]
+    const int L = 1 << tile_log2;
+    const int64_t tile = blockIdx.x;
+    const int64_t l0 = tile << tile_log2;
+    const bool vec = (d & 3) == 0;
+    for (int32_t j = 0; j < r; ++j) {
+        float *buf = rowbuf + (j & 1) * L;
+        const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
+        const uint16_t *sj = srcp + (int64_t)j * rowlen;
+        const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+        const float *lj = lk + (int64_t)j * rowlen;
+        for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
+            const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
+            const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+            const float4 v = *reinterpret_cast<const float4 *>(lj + at);
+            const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
+                           s3 = packed.y >> 16;
+            if (s0 != kSrcPad) buf[s0 & 0x7fffu] = (s0 & 0x8000u) ? -v.x : v.x;
+            if (s1 != kSrcPad) buf[s1 & 0x7fffu] = (s1 & 0x8000u) ? -v.y : v.y;
+            if (s2 != kSrcPad) buf[s2 & 0x7fffu] = (s2 & 0x8000u) ? -v.z : v.z;
+            if (s3 != kSrcPad) buf[s3 & 0x7fffu] = (s3 & 0x8000u) ? -v.w : v.w;
+        }
+        __syncthreads();   // the other buffer is free again once every thread has passed this barrier
+        float *out = rowest + (int64_t)j * d + l0;
+        if (vec) {
+            for (int p = threadIdx.x * 4; p < L && l0 + p < d; p += blockDim.x * 4)
+                *reinterpret_cast<float4 *>(out + p) = *reinterpret_cast<const float4 *>(buf + p);
+        } else {
+            for (int p = threadIdx.x; p < L && l0 + p < d; p += blockDim.x) out[p] = buf[p];
+        }
+    }
+}
+
+int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *rowest)
+{
+    Plan &pl = ctx->plan;
+    const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
+    float *lk = pl.stg;                                              // the staging buffer is idle between two sketches
+    {
+        ProfScope ps(ctx, KID_BIN_LOOKUP);
+        hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)pl.nbins, (unsigned)ctx->r), dim3(1024), (size_t)(W * 4),
+                           ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
+    }
+    {
+        ProfScope ps(ctx, KID_BIN_COLLECT);
+        hipLaunchKernelGGL(k_bin_collect, dim3((unsigned)pl.ntile), dim3(1024), (size_t)(2 * L * 4), ctx->stream,
+                           lk, pl.srcp, pl.dst16, pl.pbase, rowest, ctx->r, ctx->d, pl.tile_log2, pl.ntile,
+                           pl.rowlen);
+    }
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // small tables: the whole row fits in LDS; accumulate there, then add the partial rows to memory
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
@@ -511,6 +602,8 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(CH * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(W * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((NB + 1) * 4));
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         rc = dispatch_acc(ctx, nullptr, true);
@@ -559,6 +652,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen / kRunPad) * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * r * rowlen * 4);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.rowest, r * ctx->d * 4);
         if (rc != SAMS_OK) break;
         e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess)
@@ -591,12 +685,12 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
 void plan_destroy(sams_ctx *ctx)
 {
     Plan &pl = ctx->plan;
-    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.stg};
+    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.stg, pl.rowest};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     pl.srcp = nullptr;
     pl.dst16 = pl.pbase = pl.binbase = pl.meta = nullptr;
-    pl.stg = nullptr;
+    pl.stg = pl.rowest = nullptr;
 }
 
 int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)

@@ -47,6 +47,21 @@ k_estimate(const float *__restrict__ S, const float *__restrict__ vhat, float *_
     est[l] = vhat ? (med / sqrtf(vhat[l])) : med;
 }
 
+// est[l] = median_j(rowest[j][l]) / sqrt(vhat[l]) from row estimates already in coordinate order
+template <int R>
+__global__ void __launch_bounds__(256)
+k_est_median(const float *__restrict__ rowest, const float *__restrict__ vhat, float *__restrict__ est,
+             int64_t d)
+{
+    int64_t l = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (l >= d) return;
+    float a[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) a[j] = rowest[(int64_t)j * d + l];
+    float med = median_of<R>(a);
+    est[l] = vhat ? (med / sqrtf(vhat[l])) : med;
+}
+
 // ------------------------------------------------------------------------------------------
 // stage 3b: exact top-k of |est| by radix selection on the 31-bit magnitude pattern
 // ------------------------------------------------------------------------------------------
@@ -228,6 +243,24 @@ int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, floa
 {
     const int block = 256;
     const int grid = grid_for(ctx->d, block);
+    if (ctx->plan.mode == PLAN_BINNED && g_tun.estimate_path == 0) {
+        SAMS_TRY(enqueue_row_estimates_planned(ctx, S_mean, ctx->plan.rowest));
+        switch (ctx->r) {
+#define SAMS_CASE(R)                                                                                  \
+    case R:                                                                                           \
+        SAMS_LAUNCH(ctx, KID_EST_MEDIAN, (k_est_median<R>), grid, block, ctx->plan.rowest, vhat, est, \
+                    ctx->d);                                                                          \
+        break;
+            SAMS_CASE(1) SAMS_CASE(2) SAMS_CASE(3) SAMS_CASE(4) SAMS_CASE(5) SAMS_CASE(6) SAMS_CASE(7)
+            SAMS_CASE(8) SAMS_CASE(9) SAMS_CASE(10) SAMS_CASE(11) SAMS_CASE(12) SAMS_CASE(13)
+            SAMS_CASE(14) SAMS_CASE(15) SAMS_CASE(16)
+#undef SAMS_CASE
+        default:
+            return SAMS_EINVAL;
+        }
+        SAMS_HIP(hipGetLastError());
+        return SAMS_OK;
+    }
     switch (ctx->r) {
 #define SAMS_CASE(R)                                                                             \
     case R:                                                                                      \

@@ -27,15 +27,17 @@ def sams():
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
     "default": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32, scatter_threads=1024,
-                    sketch_path=0),
+                    sketch_path=0, estimate_path=0),
     "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=16,
-                                 scatter_threads=256, sketch_path=0),
+                                 scatter_threads=256, sketch_path=0, estimate_path=0),
     "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, run_pad=32,
-                          scatter_threads=512, sketch_path=0),
+                          scatter_threads=512, sketch_path=0, estimate_path=0),
     "binned-unroll2": dict(tile_log2=12, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=16,
-                           scatter_threads=1024, sketch_path=0),
+                           scatter_threads=1024, sketch_path=0, estimate_path=0),
     "global-atomic": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
-                          scatter_threads=1024, sketch_path=1),
+                          scatter_threads=1024, sketch_path=1, estimate_path=0),
+    "estimate-by-gathers": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
+                                scatter_threads=1024, sketch_path=0, estimate_path=1),
 }
 
 
@@ -155,7 +157,7 @@ def test_sketch_reduce_bit_exact(sams, n, r, c):
 
 @pytest.mark.parametrize("d,n,r,c,k", SHAPES)
 @pytest.mark.parametrize("use_vhat", [True, False])
-def test_estimates_and_topk_bit_exact(sams, d, n, r, c, k, use_vhat):
+def test_estimates_and_topk_bit_exact(sams, path, d, n, r, c, k, use_vhat):
     rng = np.random.default_rng(d + r)
     hp = inputs.hash_params(r, seed=5)
     S = (rng.standard_normal((r, c)) * 10.0 ** rng.uniform(-3, 0, (r, c))).astype(np.float32)
