@@ -37,6 +37,10 @@ def kernel_algorithmic_bytes(name, d, n, r, c, k):
         "k_bin_scatter": 4 * n * d,             # reads u once; the staging it writes is not algorithmic
         "k_bin_accumulate": n * rc4,            # writes every table cell once; the staging it reads is not
         "k_sketch_lds": 4 * n * d + n * rc4,
+        "k_head_scatter": 20 * n * d + 12 * d,  # the head's own traffic; the staging it also writes is not
+        "k_bin_lookup": rc4,                    # reads the mean table once
+        "k_bin_collect": None,                  # moves only scratch
+        "k_est_median": 4 * d + 4 * d,          # vhat read, estimates written
         "k_reduce": (n + 1) * rc4,
         "k_estimate": rc4 + 4 * d + 4 * d,
         "k_sel_hist": 4 * d,
@@ -89,7 +93,8 @@ def main():
     ap.add_argument("--cpu-sample-d", type=int, default=2_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept resident")
-    ap.add_argument("--tune", default="", help="library tunables, e.g. tile_log2=14,win_log2=15")
+    ap.add_argument("--tune", default="fuse_head=1",
+                    help="library tunables (sams_configure), e.g. fuse_head=1,tile_log2=14,win_log2=15")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the n workers are batched buffers on it); "
@@ -168,7 +173,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: d={d}, n={n} simulated workers, sketch {r}x{c}, k={k}, "
                                f"{w.noise} gradients in {w.nseg} segments + {w.heavy} heavy coordinates",
-                   "d": d, "n": n, "r": r, "c": c, "k": k},
+                   "d": d, "n": n, "r": r, "c": c, "k": k, "tunables": args.tune},
         "worker_coords_per_s": n * d / (ms_per_step * 1e-3),
         "device_ms_per_step": ev_ms_per_step,
         "step_algorithmic_bytes": step_bytes,

@@ -66,9 +66,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
  *   "tile_log2"   6..14 (default 14): log2 of the coordinates per tile of the binned sketch path
- *   "win_log2"    4..15 (default 14): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
+ *   "win_log2"    4..15 (default 15): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
  *                 accumulated row by row in LDS, larger ones through the binned path
- *   "chunk_log2"  6..11 (default 10): log2 of the stream positions the binned accumulation handles
+ *   "chunk_log2"  6..11 (default 11): log2 of the stream positions the binned accumulation handles
  *                 between two barriers
  *   "acc_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned accumulation; must not
  *                 exceed 2^chunk_log2, and a window plus two chunks of 8 bytes must fit in 160 KiB of LDS
@@ -76,6 +76,10 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "run_pad"     16 or 32 (default 32): stream positions a (tile, window) run is padded to, so that the
  *                 staging writes cover whole 64- or 128-byte lines
  *   "scatter_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned scatter pass
+ *   "fuse_head"   0 (default) or 1: with 1, amsgrad_ef_update (when it runs the head and the context uses
+ *                 the binned path) also writes the sorted copy of e_u that sketch_accumulate needs, and a
+ *                 following sketch_accumulate called with that same e_u pointer skips its first pass.
+ *                 The caller must then not write to e_u between the two calls (the algorithm never does).
  *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
  *                 1: one gather per (row, coordinate) straight from the table
  *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)

@@ -9,13 +9,13 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {14, 14, 10, 1024, 0, 1024, 0, 32};
+Tunables g_tun = {14, 15, 11, 1024, 0, 1024, 0, 0, 32};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
     "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds", "k_bin_lookup",
-    "k_bin_collect", "k_est_median"};
+    "k_bin_collect", "k_est_median", "k_head_scatter"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -172,6 +172,9 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "estimate_path")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.estimate_path = value;
+    } else if (!strcmp(key, "fuse_head")) {
+        if (value < 0 || value > 1) return SAMS_EINVAL;
+        g_tun.fuse_head = value;
     } else if (!strcmp(key, "run_pad")) {
         if (value != 16 && value != 32) return SAMS_EINVAL;
         g_tun.run_pad = value;
@@ -271,8 +274,14 @@ int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, 
     if (!aligned16(g_next) || !aligned16(m) || !aligned16(e_u) || !aligned16(v) || !aligned16(vhat) ||
         !aligned16(x) || !aligned16(idx) || !aligned16(delta))
         return SAMS_EINVAL;
+    ctx->plan.staged_u = nullptr;                                    // e_u is about to change
     SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
-    if (g_next) SAMS_TRY(enqueue_head(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
+    if (g_next) {
+        if (head_can_fuse(ctx))
+            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
+        else
+            SAMS_TRY(enqueue_head(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
+    }
     return SAMS_OK;
 }
 

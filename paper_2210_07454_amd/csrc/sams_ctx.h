@@ -44,7 +44,7 @@ enum KernelId {
     KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
     KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
     KID_GATHER, KID_PLAN_BUILD, KID_BIN_SCATTER, KID_BIN_ACCUMULATE, KID_SKETCH_LDS, KID_BIN_LOOKUP,
-    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_COUNT
+    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_COUNT
 };
 const char *kernel_name(int kid);
 
@@ -69,6 +69,7 @@ struct Plan {
     uint32_t *binbase;  // [r][nbins+1]     start of each bin in the row stream (multiples of the chunk)
     uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags
     float *stg;         // [n][r][rowlen]       per-step staging: signed values at their stream positions
+    const float *staged_u;  // vector whose sorted copy the staging holds (set by a fused head), else null
     float *rowest;      // [r][d]               per-step: signed row estimates in coordinate order (stage 3)
 };
 
@@ -81,6 +82,7 @@ struct Tunables {
     int sketch_path;   // 0 = choose from c, 1 = force the global-atomic kernel
     int scatter_threads;  // workgroup size of the scatter kernel
     int estimate_path;    // 0 = stage 3 through the plan when there is one, 1 = direct gathers from the table
+    int fuse_head;        // 1 = amsgrad_ef_update also stages u for the next sketch_accumulate
     int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
 };
 extern Tunables g_tun;
@@ -165,6 +167,9 @@ int plan_create(sams_ctx *ctx, const Tunables &tun);
 void plan_destroy(sams_ctx *ctx);
 int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers);
 int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *rowest);
+bool head_can_fuse(const sams_ctx *ctx);
+int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
+                         float beta1, float beta2, float rho);
 // sams_select.hip
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
 int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel);

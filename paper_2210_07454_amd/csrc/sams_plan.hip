@@ -33,12 +33,31 @@ namespace sams {
 constexpr int kPlanThreads = 1024;
 constexpr int kScatterThreads = 256;
 constexpr int kNumXcd = 8;
+constexpr int kAccDepth = 4;                // chunks in flight per workgroup of the accumulate kernel
 constexpr int kRunPad = 16;                 // slot-group granularity in elements (64 bytes); runs are padded to a multiple of it
 
 constexpr uint16_t kSrcPad = 0x7fffu;          // slot source meaning "padding": tiles hold at most 2^14 coordinates
 constexpr uint32_t kMetaNextShift = 15;
 constexpr uint32_t kMetaHasNext = 1u << 26;
 constexpr uint32_t kMetaNotFirst = 1u << 27;   // padding, or a position some earlier position adds
+
+// streaming accesses: data touched once per step should not push the shared metadata out of L2
+__device__ __forceinline__ void store_stream(float4 *p, const float4 &v)
+{
+    __builtin_nontemporal_store(v.x, &p->x);
+    __builtin_nontemporal_store(v.y, &p->y);
+    __builtin_nontemporal_store(v.z, &p->z);
+    __builtin_nontemporal_store(v.w, &p->w);
+}
+__device__ __forceinline__ float4 load_stream(const float4 *p)
+{
+    float4 v;
+    v.x = __builtin_nontemporal_load(&p->x);
+    v.y = __builtin_nontemporal_load(&p->y);
+    v.z = __builtin_nontemporal_load(&p->z);
+    v.w = __builtin_nontemporal_load(&p->w);
+    return v;
+}
 
 __host__ __device__ __forceinline__ int pad_run(int len, int pad) { return (len + pad - 1) & ~(pad - 1); }
 
@@ -285,7 +304,7 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
         if (vec) {
             for (int p = threadIdx.x * 4; p < L; p += blockDim.x * 4) {
                 float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (l0 + p < d) q = *reinterpret_cast<const float4 *>(ui + l0 + p);
+                if (l0 + p < d) q = load_stream(reinterpret_cast<const float4 *>(ui + l0 + p));
                 *reinterpret_cast<float4 *>(tilebuf + p) = q;
             }
         } else {
@@ -307,10 +326,113 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
                 v.y = (s1 == kSrcPad) ? 0.f : tilebuf[s1 & 0x7fffu]; v.y = (s1 & 0x8000u) ? -v.y : v.y;
                 v.z = (s2 == kSrcPad) ? 0.f : tilebuf[s2 & 0x7fffu]; v.z = (s2 & 0x8000u) ? -v.z : v.z;
                 v.w = (s3 == kSrcPad) ? 0.f : tilebuf[s3 & 0x7fffu]; v.w = (s3 & 0x8000u) ? -v.w : v.w;
-                *reinterpret_cast<float4 *>(oj + at) = v;
+                store_stream(reinterpret_cast<float4 *>(oj + at), v);
             }
         }
         __syncthreads();
+    }
+}
+
+// Pass 1 fused with the head of Alg. 2 (the m, u, h, v, vhat lines; see k_head): the tile of u that pass 1
+// needs in LDS is produced on the spot from g, m and e, so u is never read back from memory.  The
+// arithmetic is the same, operation for operation, as in the separate head kernel.  1024 threads, each
+// owning the same 4-coordinate groups for every worker so that the worker sum of g stays in registers.
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedIters = 4;      // tiles of at most 2^14 coordinates = 4 float4 per thread
+
+struct HeadArgs {
+    const float *g;
+    float *m, *e, *v, *vhat;
+    const uint32_t *bitmap;
+    float beta1, omb1, beta2, omb2, rho;
+};
+
+__global__ void __launch_bounds__(kFusedThreads)
+k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
+               const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, int32_t r, int64_t d,
+               int tile_log2, int64_t ntile, int64_t rowlen)
+{
+    extern __shared__ float tilebuf[];
+    const int L = 1 << tile_log2;
+    const int64_t per = (ntile + kNumXcd - 1) / kNumXcd;
+    const int64_t tile = (int64_t)(blockIdx.x % kNumXcd) * per + blockIdx.x / kNumXcd;
+    if (tile >= ntile) return;
+    const int64_t l0 = tile << tile_log2;
+    float gs[kFusedIters][4];
+    uint32_t selbits[kFusedIters];
+#pragma unroll
+    for (int it = 0; it < kFusedIters; ++it) {
+        const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+        selbits[it] = 0;
+        if (p < L && l0 + p < d) selbits[it] = (ha.bitmap[(l0 + p) >> 5] >> ((l0 + p) & 31)) & 0xFu;
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t wbase = (int64_t)i * d + l0;
+#pragma unroll
+        for (int it = 0; it < kFusedIters; ++it) {
+            const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+            if (p < L) {
+                float uv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (l0 + p < d) {
+                    const float4 a = load_stream(reinterpret_cast<const float4 *>(ha.g + wbase + p));
+                    const float4 b = load_stream(reinterpret_cast<const float4 *>(ha.m + wbase + p));
+                    const float4 cc = load_stream(reinterpret_cast<const float4 *>(ha.e + wbase + p));
+                    const float gv[4] = {a.x, a.y, a.z, a.w}, mv[4] = {b.x, b.y, b.z, b.w},
+                                ev[4] = {cc.x, cc.y, cc.z, cc.w};
+                    float mo[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float mm = (ha.beta1 * mv[t]) + (ha.omb1 * gv[t]);
+                        const float ein = ((selbits[it] >> t) & 1u) ? 0.0f : ev[t];   // e_t is zero on I_t
+                        mo[t] = mm;
+                        uv[t] = mm + (ha.rho * ein);
+                        gs[it][t] = (i == 0) ? gv[t] : (gs[it][t] + gv[t]);
+                    }
+                    store_stream(reinterpret_cast<float4 *>(ha.m + wbase + p), make_float4(mo[0], mo[1], mo[2], mo[3]));
+                    store_stream(reinterpret_cast<float4 *>(ha.e + wbase + p), make_float4(uv[0], uv[1], uv[2], uv[3]));
+                }
+                *reinterpret_cast<float4 *>(tilebuf + p) = make_float4(uv[0], uv[1], uv[2], uv[3]);
+            }
+        }
+        __syncthreads();
+        for (int32_t j = 0; j < r; ++j) {
+            const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
+            const uint16_t *sj = srcp + (int64_t)j * rowlen;
+            const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+            float *oj = stg + ((int64_t)i * r + j) * rowlen;
+            for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
+                const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
+                const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+                const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
+                               s3 = packed.y >> 16;
+                float4 v;
+                v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
+                v.y = (s1 == kSrcPad) ? 0.f : tilebuf[s1 & 0x7fffu]; v.y = (s1 & 0x8000u) ? -v.y : v.y;
+                v.z = (s2 == kSrcPad) ? 0.f : tilebuf[s2 & 0x7fffu]; v.z = (s2 & 0x8000u) ? -v.z : v.z;
+                v.w = (s3 == kSrcPad) ? 0.f : tilebuf[s3 & 0x7fffu]; v.w = (s3 & 0x8000u) ? -v.w : v.w;
+                store_stream(reinterpret_cast<float4 *>(oj + at), v);
+            }
+        }
+        __syncthreads();
+    }
+    const float fn = (float)n;
+#pragma unroll
+    for (int it = 0; it < kFusedIters; ++it) {
+        const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+        if (p < L && l0 + p < d) {
+            const float4 vin = *reinterpret_cast<const float4 *>(ha.v + l0 + p);
+            const float4 hin = *reinterpret_cast<const float4 *>(ha.vhat + l0 + p);
+            float vv[4] = {vin.x, vin.y, vin.z, vin.w}, vh[4] = {hin.x, hin.y, hin.z, hin.w};
+            bool moved = false;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float h = ((selbits[it] >> t) & 1u) ? (gs[it][t] / fn) : 0.0f;
+                vv[t] = (ha.beta2 * vv[t]) + (ha.omb2 * (h * h));
+                if (vv[t] > vh[t]) { vh[t] = vv[t]; moved = true; }
+            }
+            *reinterpret_cast<float4 *>(ha.v + l0 + p) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+            if (moved) *reinterpret_cast<float4 *>(ha.vhat + l0 + p) = make_float4(vh[0], vh[1], vh[2], vh[3]);
+        }
     }
 }
 
@@ -343,48 +465,58 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     const uint32_t *m = meta + (int64_t)j * rowlen + b0;
     const int64_t nchunk = (b1 - b0) / CH;
     const uint32_t wmask = (uint32_t)W - 1u;
-    float cv[UNROLL];
-    uint32_t cm[UNROLL];
-    if (nchunk > 0) {
+    // register ring of kAccDepth chunks: the loads of chunk q + kAccDepth are issued while chunk q is processed
+    float rv[kAccDepth][UNROLL];
+    uint32_t rm[kAccDepth][UNROLL];
 #pragma unroll
-        for (int z = 0; z < UNROLL; ++z) {
-            cv[z] = v[z * THREADS + threadIdx.x];
-            cm[z] = m[z * THREADS + threadIdx.x];
-        }
-    }
-    for (int64_t q = 0; q < nchunk; ++q) {
-        float nv[UNROLL];
-        uint32_t nm[UNROLL];
-        if (q + 1 < nchunk) {                                        // prefetch the next chunk
+    for (int s = 0; s < kAccDepth; ++s) {
+        if (s < nchunk) {
 #pragma unroll
             for (int z = 0; z < UNROLL; ++z) {
-                nv[z] = v[(q + 1) * CH + z * THREADS + threadIdx.x];
-                nm[z] = m[(q + 1) * CH + z * THREADS + threadIdx.x];
+                rv[s][z] = __builtin_nontemporal_load(v + (int64_t)s * CH + z * THREADS + threadIdx.x);
+                rm[s][z] = m[(int64_t)s * CH + z * THREADS + threadIdx.x];
             }
         }
-        uint2 *xb = xbuf + (q & 1) * CH;
+    }
+    for (int64_t q0 = 0; q0 < nchunk; q0 += kAccDepth) {
 #pragma unroll
-        for (int z = 0; z < UNROLL; ++z)
-            xb[z * THREADS + threadIdx.x] = make_uint2(__float_as_uint(cv[z]), cm[z]);
-        __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+        for (int s = 0; s < kAccDepth; ++s) {
+            const int64_t q = q0 + s;
+            if (q < nchunk) {                                        // uniform over the workgroup
+                float cv[UNROLL];
+                uint32_t cm[UNROLL];
 #pragma unroll
-        for (int z = 0; z < UNROLL; ++z) {
-            uint32_t word = cm[z];
-            if (!(word & kMetaNotFirst)) {
-                const uint32_t w = word & wmask;
-                float x = win[w] + cv[z];
-                while (word & kMetaHasNext) {
-                    uint2 e = xb[(word >> kMetaNextShift) & (CH - 1)];
-                    x = x + __uint_as_float(e.x);
-                    word = e.y;
+                for (int z = 0; z < UNROLL; ++z) {
+                    cv[z] = rv[s][z];
+                    cm[z] = rm[s][z];
                 }
-                win[w] = x;
-            }
-        }
+                if (q + kAccDepth < nchunk) {
 #pragma unroll
-        for (int z = 0; z < UNROLL; ++z) {
-            cv[z] = nv[z];
-            cm[z] = nm[z];
+                    for (int z = 0; z < UNROLL; ++z) {
+                        rv[s][z] = __builtin_nontemporal_load(v + (q + kAccDepth) * CH + z * THREADS + threadIdx.x);
+                        rm[s][z] = m[(q + kAccDepth) * CH + z * THREADS + threadIdx.x];
+                    }
+                }
+                uint2 *xb = xbuf + (q & 1) * CH;
+#pragma unroll
+                for (int z = 0; z < UNROLL; ++z)
+                    xb[z * THREADS + threadIdx.x] = make_uint2(__float_as_uint(cv[z]), cm[z]);
+                __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+#pragma unroll
+                for (int z = 0; z < UNROLL; ++z) {
+                    uint32_t word = cm[z];
+                    if (!(word & kMetaNotFirst)) {
+                        const uint32_t w = word & wmask;
+                        float x = win[w] + cv[z];
+                        while (word & kMetaHasNext) {
+                            uint2 e = xb[(word >> kMetaNextShift) & (CH - 1)];
+                            x = x + __uint_as_float(e.x);
+                            word = e.y;
+                        }
+                        win[w] = x;
+                    }
+                }
+            }
         }
     }
     __syncthreads();
@@ -423,7 +555,7 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta
     const int64_t n4 = (b1 - b0) >> 2;                               // bins are whole chunks: a multiple of 4
     for (int64_t q = threadIdx.x; q < n4; q += blockDim.x) {
         const uint4 w = m4[q];
-        o4[q] = make_float4(win[w.x & wmask], win[w.y & wmask], win[w.z & wmask], win[w.w & wmask]);
+        store_stream(o4 + q, make_float4(win[w.x & wmask], win[w.y & wmask], win[w.z & wmask], win[w.w & wmask]));
     }
 }
 
@@ -446,7 +578,7 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
         for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
             const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
             const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
-            const float4 v = *reinterpret_cast<const float4 *>(lj + at);
+            const float4 v = load_stream(reinterpret_cast<const float4 *>(lj + at));
             const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
                            s3 = packed.y >> 16;
             if (s0 != kSrcPad) buf[s0 & 0x7fffu] = (s0 & 0x8000u) ? -v.x : v.x;
@@ -458,7 +590,7 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
         float *out = rowest + (int64_t)j * d + l0;
         if (vec) {
             for (int p = threadIdx.x * 4; p < L && l0 + p < d; p += blockDim.x * 4)
-                *reinterpret_cast<float4 *>(out + p) = *reinterpret_cast<const float4 *>(buf + p);
+                store_stream(reinterpret_cast<float4 *>(out + p), *reinterpret_cast<const float4 *>(buf + p));
         } else {
             for (int p = threadIdx.x; p < L && l0 + p < d; p += blockDim.x) out[p] = buf[p];
         }
@@ -602,6 +734,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(CH * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(W * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((NB + 1) * 4));
@@ -693,6 +826,29 @@ void plan_destroy(sams_ctx *ctx)
     pl.stg = pl.rowest = nullptr;
 }
 
+bool head_can_fuse(const sams_ctx *ctx)
+{
+    return g_tun.fuse_head && ctx->plan.mode == PLAN_BINNED && (ctx->d & 3) == 0 && ctx->plan.tile_log2 <= 14;
+}
+
+int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
+                         float beta1, float beta2, float rho)
+{
+    Plan &pl = ctx->plan;
+    const int64_t L = (int64_t)1 << pl.tile_log2;
+    const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
+    HeadArgs ha = {g, m, e_u, v, vhat, ctx->bitmap, beta1, 1.0f - beta1, beta2, 1.0f - beta2, rho};
+    {
+        ProfScope ps(ctx, KID_HEAD_SCATTER);
+        hipLaunchKernelGGL(k_head_scatter, dim3((unsigned)(per * kNumXcd)), dim3(kFusedThreads), (size_t)(L * 4),
+                           ctx->stream, ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, ctx->r, ctx->d,
+                           pl.tile_log2, pl.ntile, pl.rowlen);
+    }
+    SAMS_HIP(hipGetLastError());
+    pl.staged_u = e_u;          // the staging now holds the sorted copy of this vector
+    return SAMS_OK;
+}
+
 int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
 {
     Plan &pl = ctx->plan;
@@ -713,7 +869,7 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
         return SAMS_OK;
     }
     const int64_t L = (int64_t)1 << pl.tile_log2;
-    {
+    if (pl.staged_u != u) {                                          // not staged by a fused head: pass 1 now
         const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
         ProfScope ps(ctx, KID_BIN_SCATTER);
         hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3((unsigned)g_tun.scatter_threads),

@@ -26,18 +26,22 @@ def sams():
 
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
-    "default": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32, scatter_threads=1024,
-                    sketch_path=0, estimate_path=0),
+    "default": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32, scatter_threads=1024,
+                    sketch_path=0, estimate_path=0, fuse_head=0),
     "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=16,
-                                 scatter_threads=256, sketch_path=0, estimate_path=0),
+                                 scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0),
     "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, run_pad=32,
-                          scatter_threads=512, sketch_path=0, estimate_path=0),
+                          scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=0),
     "binned-unroll2": dict(tile_log2=12, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=16,
-                           scatter_threads=1024, sketch_path=0, estimate_path=0),
-    "global-atomic": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
-                          scatter_threads=1024, sketch_path=1, estimate_path=0),
+                           scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=0),
+    "global-atomic": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32,
+                          scatter_threads=1024, sketch_path=1, estimate_path=0, fuse_head=0),
+    "fused-head": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
+                       scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=1),
+    "fused-head-small-tiles": dict(tile_log2=9, win_log2=7, chunk_log2=9, acc_threads=256, run_pad=16,
+                                   scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=1),
     "estimate-by-gathers": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
-                                scatter_threads=1024, sketch_path=0, estimate_path=1),
+                                scatter_threads=1024, sketch_path=0, estimate_path=1, fuse_head=0),
 }
 
 
@@ -213,7 +217,7 @@ def test_gather_topk_bit_exact(sams, d, n, r, c, k):
 
 
 @pytest.mark.parametrize("d,n,r,c,k", SHAPES)
-def test_amsgrad_ef_update_head_and_tail_bit_exact(sams, d, n, r, c, k):
+def test_amsgrad_ef_update_head_and_tail_bit_exact(sams, path, d, n, r, c, k):
     rng = np.random.default_rng(d + 1)
     o = Oracle("f32")
     b1, b2, lr = 0.9, 0.99, 1e-3
