@@ -80,6 +80,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 the binned path) also writes the sorted copy of e_u that sketch_accumulate needs, and a
  *                 following sketch_accumulate called with that same e_u pointer skips its first pass.
  *                 The caller must then not write to e_u between the two calls (the algorithm never does).
+ *   "stage_rows"  0..16 (default 0 = all r rows): rows of the sketch staged at once on the binned path; the
+ *                 staging buffer holds 4*n*stage_rows*(1.1 to 1.5)*d bytes and stage 1 runs row group after
+ *                 row group (each group after the first re-reads u)
  *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
  *                 1: one gather per (row, coordinate) straight from the table
  *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)

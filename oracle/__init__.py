@@ -108,14 +108,15 @@ class Oracle:
         self._fn("orc_sketch_mean")(_p(S_w), ctypes.c_int32(n), ctypes.c_int32(r), ctypes.c_int64(c), _p(out))
         return out
 
-    def unsketch(self, S, vhat, d, hash_params):
+    def unsketch(self, S, vhat, d, hash_params, l0=0):
+        """Estimates of the d coordinates l0 .. l0+d-1 (vhat, if given, holds those d entries)."""
         hp = np.ascontiguousarray(hash_params, dtype=np.uint32)
         self._chk(S, vhat)
         r, c = S.shape
         assert hp.shape[0] == r
         est = np.empty(d, dtype=self.dtype)
         self._fn("orc_unsketch")(_p(S), _p(vhat), ctypes.c_int64(d), ctypes.c_int32(r),
-                                 ctypes.c_int64(c), _p(hp), _p(est))
+                                 ctypes.c_int64(c), _p(hp), _p(est), ctypes.c_int64(l0))
         return est
 
     def topk(self, est, k):

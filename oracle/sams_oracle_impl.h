@@ -71,12 +71,15 @@ void FN(orc_sketch_mean)(const REAL *S_w /* [n][r][c] */, int32_t n, int32_t r, 
 
 /* Sec. II-C + Alg. 3: est_l = median_j( s_j(l) S[j,h_j(l)] ) / sqrt(vhat_l);
  * vhat == NULL gives the plain operator U_0.  Median = element floor((r-1)/2) of the
- * ascending sort of the r row estimates. */
+ * ascending sort of the r row estimates.  The d coordinates l0 .. l0+d-1 are recovered;
+ * vhat and est are indexed from l0 (l0 = 0 for the whole vector). */
 void FN(orc_unsketch)(const REAL *S /* [r][c] */, const REAL *vhat /* [d] or NULL */,
-                      int64_t d, int32_t r, int64_t c, const uint32_t *hash, REAL *est /* [d] */)
+                      int64_t d, int32_t r, int64_t c, const uint32_t *hash, REAL *est /* [d] */,
+                      int64_t l0)
 {
     REAL vals[64];
-    for (int64_t l = 0; l < d; ++l) {
+    for (int64_t t = 0; t < d; ++t) {
+        const int64_t l = l0 + t;
         for (int32_t j = 0; j < r; ++j) {
             const uint32_t *hp = hash + 4 * j;
             int64_t b = orc_bucket(hp[0], hp[1], (uint32_t)l, c);
@@ -91,7 +94,7 @@ void FN(orc_unsketch)(const REAL *S /* [r][c] */, const REAL *vhat /* [d] or NUL
             vals[p + 1] = key;
         }
         REAL med = vals[(r - 1) / 2];
-        est[l] = vhat ? med / FN(orc_sqrt)(vhat[l]) : med;
+        est[t] = vhat ? med / FN(orc_sqrt)(vhat[t]) : med;
     }
 }
 
@@ -200,7 +203,7 @@ int FN(orc_step)(const REAL *g, REAL *m, REAL *e_u, REAL *v, REAL *vhat, REAL *x
     for (int32_t i = 0; i < n; ++i)
         FN(orc_sketch)(e_u + (int64_t)i * d, d, r, c, hash, S_w + (int64_t)i * r * c);
     FN(orc_sketch_mean)(S_w, n, r, c, S_mean);
-    FN(orc_unsketch)(S_mean, use_vhat ? vhat : NULL, d, r, c, hash, est);
+    FN(orc_unsketch)(S_mean, use_vhat ? vhat : NULL, d, r, c, hash, est, 0);
     if (FN(orc_topk)(est, d, k, idx) != 0) return -1;
     FN(orc_gather)(e_u, use_vhat ? vhat : NULL, idx, k, n, d, U_w, delta);
     FN(orc_tail)(e_u, x, idx, delta, k, n, d, lr);

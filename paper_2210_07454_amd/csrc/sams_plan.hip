@@ -59,6 +59,12 @@ __device__ __forceinline__ float4 load_stream(const float4 *p)
     return v;
 }
 
+// Rows [j0, j0 + rj) of the r rows are handled by one launch; their staging is stg[n][sr][rowlen] with
+// row j at slot j - j0 (sr = rows the staging buffer was sized for, r in total).
+struct RowGroup {
+    int32_t j0, rj, sr, r;
+};
+
 __host__ __device__ __forceinline__ int pad_run(int len, int pad) { return (len + pad - 1) & ~(pad - 1); }
 
 // ------------------------------------------------------------------------------------------
@@ -289,7 +295,7 @@ k_plan_chain(int chunk_log2, int64_t rowlen, uint32_t *__restrict__ meta)
 // stream position, 4 LDS reads and one 16-byte store -- nothing depends on another global load.
 __global__ void __launch_bounds__(1024)
 k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
-              const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, int32_t r, int64_t d,
+              const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
               int tile_log2, int64_t ntile, int64_t rowlen)
 {
     extern __shared__ float tilebuf[];
@@ -311,11 +317,11 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
             for (int p = threadIdx.x; p < L; p += blockDim.x) tilebuf[p] = (l0 + p < d) ? ui[l0 + p] : 0.f;
         }
         __syncthreads();
-        for (int32_t j = 0; j < r; ++j) {
+        for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
             const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
             const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
-            float *oj = stg + ((int64_t)i * r + j) * rowlen;
+            float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
             for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
                 const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
                 const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
@@ -349,7 +355,7 @@ struct HeadArgs {
 
 __global__ void __launch_bounds__(kFusedThreads)
 k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
-               const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, int32_t r, int64_t d,
+               const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
                int tile_log2, int64_t ntile, int64_t rowlen)
 {
     extern __shared__ float tilebuf[];
@@ -395,11 +401,11 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
             }
         }
         __syncthreads();
-        for (int32_t j = 0; j < r; ++j) {
+        for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
             const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
             const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
-            float *oj = stg + ((int64_t)i * r + j) * rowlen;
+            float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
             for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
                 const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
                 const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
@@ -444,7 +450,7 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
 template <int THREADS, int UNROLL>
 __global__ void __launch_bounds__(THREADS)
 k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ meta,
-                 const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, int32_t r,
+                 const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg,
                  int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
 {
     constexpr int CH = THREADS * UNROLL;
@@ -456,12 +462,12 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     const int64_t slot = id / kNumXcd;
     const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
     const int32_t i = (int32_t)(slot % n);
-    if (group >= (int64_t)r * nbins) return;
-    const int32_t j = (int32_t)(group / nbins);
+    if (group >= (int64_t)rg.rj * nbins) return;
+    const int32_t jj = (int32_t)(group / nbins), j = rg.j0 + jj;
     const int64_t bin = group % nbins;
     for (int t = threadIdx.x; t < W; t += THREADS) win[t] = 0.f;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
-    const float *v = stg + ((int64_t)i * r + j) * rowlen + b0;
+    const float *v = stg + ((int64_t)i * rg.sr + jj) * rowlen + b0;
     const uint32_t *m = meta + (int64_t)j * rowlen + b0;
     const int64_t nchunk = (b1 - b0) / CH;
     const uint32_t wmask = (uint32_t)W - 1u;
@@ -521,7 +527,7 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     }
     __syncthreads();
     const int64_t base = bin << win_log2;
-    float *out = S + ((int64_t)i * r + j) * c + base;
+    float *out = S + ((int64_t)i * rg.r + j) * c + base;
     const int64_t lim = (c - base) < W ? (c - base) : W;
     for (int t = threadIdx.x; t < lim; t += THREADS) out[t] = win[t];
 }
@@ -537,12 +543,12 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
 __global__ void __launch_bounds__(1024)
 k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta,
              const uint32_t *__restrict__ binbase, float *__restrict__ lk, int64_t c, int win_log2,
-             int64_t nbins, int64_t rowlen)
+             int64_t nbins, int64_t rowlen, int32_t j0)
 {
     extern __shared__ float win[];
     const int W = 1 << win_log2;
     const int64_t bin = blockIdx.x;
-    const int j = blockIdx.y;
+    const int j = j0 + (int)blockIdx.y;
     const int64_t base = bin << win_log2;
     const float *Sj = S_mean + (int64_t)j * c + base;
     const int64_t lim = (c - base) < W ? (c - base) : W;
@@ -551,7 +557,7 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta
     const uint32_t wmask = (uint32_t)W - 1u;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
     const uint4 *m4 = reinterpret_cast<const uint4 *>(meta + (int64_t)j * rowlen + b0);
-    float4 *o4 = reinterpret_cast<float4 *>(lk + (int64_t)j * rowlen + b0);
+    float4 *o4 = reinterpret_cast<float4 *>(lk + (int64_t)blockIdx.y * rowlen + b0);
     const int64_t n4 = (b1 - b0) >> 2;                               // bins are whole chunks: a multiple of 4
     for (int64_t q = threadIdx.x; q < n4; q += blockDim.x) {
         const uint4 w = m4[q];
@@ -561,7 +567,7 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta
 
 __global__ void __launch_bounds__(1024)
 k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
-              const uint32_t *__restrict__ pbase, float *__restrict__ rowest, int32_t r, int64_t d,
+              const uint32_t *__restrict__ pbase, float *__restrict__ rowest, int32_t j0, int32_t rj, int64_t d,
               int tile_log2, int64_t ntile, int64_t rowlen)
 {
     extern __shared__ float rowbuf[];                                // [2][L]
@@ -569,12 +575,12 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
     const int64_t tile = blockIdx.x;
     const int64_t l0 = tile << tile_log2;
     const bool vec = (d & 3) == 0;
-    for (int32_t j = 0; j < r; ++j) {
+    for (int32_t j = j0; j < j0 + rj; ++j) {
         float *buf = rowbuf + (j & 1) * L;
         const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
         const uint16_t *sj = srcp + (int64_t)j * rowlen;
         const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
-        const float *lj = lk + (int64_t)j * rowlen;
+        const float *lj = lk + (int64_t)(j - j0) * rowlen;
         for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
             const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
             const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
@@ -602,16 +608,21 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
     Plan &pl = ctx->plan;
     const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
     float *lk = pl.stg;                                              // the staging buffer is idle between two sketches
-    {
-        ProfScope ps(ctx, KID_BIN_LOOKUP);
-        hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)pl.nbins, (unsigned)ctx->r), dim3(1024), (size_t)(W * 4),
-                           ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
-    }
-    {
-        ProfScope ps(ctx, KID_BIN_COLLECT);
-        hipLaunchKernelGGL(k_bin_collect, dim3((unsigned)pl.ntile), dim3(1024), (size_t)(2 * L * 4), ctx->stream,
-                           lk, pl.srcp, pl.dst16, pl.pbase, rowest, ctx->r, ctx->d, pl.tile_log2, pl.ntile,
-                           pl.rowlen);
+    const int64_t cap = (int64_t)ctx->n * pl.stage_rows;             // rows of looked-up values it can hold
+    for (int32_t j0 = 0; j0 < ctx->r; j0 += (int32_t)cap) {
+        const int32_t rj = (ctx->r - j0) < cap ? (ctx->r - j0) : (int32_t)cap;
+        {
+            ProfScope ps(ctx, KID_BIN_LOOKUP);
+            hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)pl.nbins, (unsigned)rj), dim3(1024), (size_t)(W * 4),
+                               ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2, pl.nbins,
+                               pl.rowlen, j0);
+        }
+        {
+            ProfScope ps(ctx, KID_BIN_COLLECT);
+            hipLaunchKernelGGL(k_bin_collect, dim3((unsigned)pl.ntile), dim3(1024), (size_t)(2 * L * 4),
+                               ctx->stream, lk, pl.srcp, pl.dst16, pl.pbase, rowest, j0, rj, ctx->d, pl.tile_log2,
+                               pl.ntile, pl.rowlen);
+        }
     }
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
@@ -660,7 +671,7 @@ static int dev_alloc(sams_ctx *ctx, void **p, int64_t bytes)
 
 // (threads, unroll) variants of the accumulate kernel, selected by acc_threads / chunk_log2
 template <int TH, int UN>
-static int launch_acc(sams_ctx *ctx, float *S_workers, bool set_attr)
+static int launch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_attr)
 {
     Plan &pl = ctx->plan;
     const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * TH * UN * sizeof(uint2);
@@ -669,21 +680,21 @@ static int launch_acc(sams_ctx *ctx, float *S_workers, bool set_attr)
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         return SAMS_OK;
     }
-    const int64_t groups = (int64_t)ctx->r * pl.nbins;
+    const int64_t groups = (int64_t)rg.rj * pl.nbins;
     const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
     ProfScope ps(ctx, KID_BIN_ACCUMULATE);
     hipLaunchKernelGGL((k_bin_accumulate<TH, UN>), dim3((unsigned)(gpad * ctx->n)), dim3(TH), lds, ctx->stream,
-                       pl.stg, pl.meta, pl.binbase, S_workers, ctx->n, ctx->r, ctx->c, pl.win_log2, pl.nbins,
+                       pl.stg, pl.meta, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins,
                        pl.rowlen);
     return SAMS_OK;
 }
 
-static int dispatch_acc(sams_ctx *ctx, float *S_workers, bool set_attr)
+static int dispatch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_attr)
 {
     const Plan &pl = ctx->plan;
     const int un = (1 << pl.chunk_log2) / pl.acc_threads;
 #define SAMS_ACC(TH, UN) \
-    if (pl.acc_threads == TH && un == UN) return launch_acc<TH, UN>(ctx, S_workers, set_attr);
+    if (pl.acc_threads == TH && un == UN) return launch_acc<TH, UN>(ctx, S_workers, rg, set_attr);
     SAMS_ACC(1024, 1) SAMS_ACC(1024, 2) SAMS_ACC(512, 1) SAMS_ACC(512, 2) SAMS_ACC(512, 4)
     SAMS_ACC(256, 1) SAMS_ACC(256, 2) SAMS_ACC(256, 4) SAMS_ACC(256, 8)
 #undef SAMS_ACC
@@ -698,6 +709,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.chunk_log2 = tun.chunk_log2;
     pl.acc_threads = tun.acc_threads;
     pl.run_pad = tun.run_pad;
+    pl.stage_rows = (tun.stage_rows <= 0 || tun.stage_rows > ctx->r) ? ctx->r : tun.stage_rows;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
     pl.mode = pl.nbins <= 1 ? PLAN_LDS_ROW : PLAN_BINNED;
@@ -739,7 +751,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((NB + 1) * 4));
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
-        rc = dispatch_acc(ctx, nullptr, true);
+        rc = dispatch_acc(ctx, nullptr, RowGroup{0, 0, 0, 0}, true);
         if (rc != SAMS_OK) break;
         {
             ProfScope ps(ctx, KID_PLAN_BUILD);
@@ -784,7 +796,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         rc = dev_alloc(ctx, (void **)&pl.srcp, r * rowlen * 2);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen / kRunPad) * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
-        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * r * rowlen * 4);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * pl.stage_rows * rowlen * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.rowest, r * ctx->d * 4);
         if (rc != SAMS_OK) break;
         e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
@@ -841,8 +853,9 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
     {
         ProfScope ps(ctx, KID_HEAD_SCATTER);
         hipLaunchKernelGGL(k_head_scatter, dim3((unsigned)(per * kNumXcd)), dim3(kFusedThreads), (size_t)(L * 4),
-                           ctx->stream, ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, ctx->r, ctx->d,
-                           pl.tile_log2, pl.ntile, pl.rowlen);
+                           ctx->stream, ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n,
+                           RowGroup{0, pl.stage_rows, pl.stage_rows, ctx->r}, ctx->d, pl.tile_log2, pl.ntile,
+                           pl.rowlen);
     }
     SAMS_HIP(hipGetLastError());
     pl.staged_u = e_u;          // the staging now holds the sorted copy of this vector
@@ -869,16 +882,20 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
         return SAMS_OK;
     }
     const int64_t L = (int64_t)1 << pl.tile_log2;
-    if (pl.staged_u != u) {                                          // not staged by a fused head: pass 1 now
-        const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
-        ProfScope ps(ctx, KID_BIN_SCATTER);
-        hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3((unsigned)g_tun.scatter_threads),
-                           (size_t)(L * 4), ctx->stream, u, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, ctx->r,
-                           ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);
+    const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
+    for (int32_t j0 = 0; j0 < ctx->r; j0 += pl.stage_rows) {
+        const RowGroup rg = {j0, (ctx->r - j0) < pl.stage_rows ? (ctx->r - j0) : pl.stage_rows, pl.stage_rows, ctx->r};
+        if (j0 > 0 || pl.staged_u != u) {                            // not staged by a fused head: pass 1 now
+            ProfScope ps(ctx, KID_BIN_SCATTER);
+            hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3((unsigned)g_tun.scatter_threads),
+                               (size_t)(L * 4), ctx->stream, u, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg,
+                               ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);
+        }
+        SAMS_HIP(hipGetLastError());
+        SAMS_TRY(dispatch_acc(ctx, S_workers, rg, false));
+        SAMS_HIP(hipGetLastError());
     }
-    SAMS_HIP(hipGetLastError());
-    SAMS_TRY(dispatch_acc(ctx, S_workers, false));
-    SAMS_HIP(hipGetLastError());
+    if (pl.stage_rows < ctx->r) pl.staged_u = nullptr;               // the staging now holds the last row group
     return SAMS_OK;
 }
 

@@ -130,6 +130,9 @@ def test_unsketch_is_rowwise_median_brute_force(r):
     rows32 = s.astype(np.float32) * S32[np.arange(r)[:, None], b]
     med32 = np.sort(rows32, axis=0)[(r - 1) // 2]
     assert np.array_equal(o32.unsketch(S32, v32, d, hp), med32 / np.sqrt(v32))
+    # a coordinate range starting at l0 gives the same numbers as the slice of the whole vector
+    assert np.array_equal(o.unsketch(S, np.ascontiguousarray(vhat[1000:2500]), 1500, hp, l0=1000),
+                          (med / np.sqrt(vhat))[1000:2500])
 
 
 def test_sketch_then_unsketch_meets_count_sketch_error_bound():
