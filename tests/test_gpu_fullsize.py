@@ -102,3 +102,105 @@ def test_full_size_second_iteration_matches_oracle(wl, full_sort, sketch_workers
             assert np.array_equal(host(b.x), st["x"]) and np.array_equal(host(b.e_u), st["e"])
     finally:
         sams.sams_configure("fuse_head", 0)
+
+
+def say(msg):
+    """Progress line on the real stderr (a silent run of several minutes looks hung from outside)."""
+    import sys
+    sys.__stderr__.write(f"[fullsize] {msg}\n")
+    sys.__stderr__.flush()
+
+
+@pytest.mark.timeout(1500)
+def test_stress_size_second_iteration_sampled():
+    """C5 (d = 1.3 G): the binned path with one sketch row staged at a time so that state, plan and staging fit
+    in HBM together.  Outputs the oracle can afford are checked in full (two whole (worker, row) tables, the mean
+    table, the gathered values), the rest on coordinate ranges at both ends of the vector, and the index set
+    through the properties that define it."""
+    from paper_2210_07454_amd import sams
+    w = inputs.WORKLOADS["C5"]
+    d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
+    free, total = torch.cuda.mem_get_info()
+    if total < 250 * 2**30:
+        pytest.skip("needs a 288 GB device")
+    tun = dict(fuse_head=1, stage_rows=1, run_pad=16)
+    for key, val in tun.items():
+        sams.sams_configure(key, val)
+    try:
+        gs = inputs.GradientStream(w, device="cuda")
+        hp = inputs.hash_params(r, seed=w.seed)
+        o = Oracle("f32")
+        edge = 16_000_000
+        ranges = [(0, edge), (d - edge, d)]
+        with sams.Context(d, n, r, c, k, hp) as ctx:
+            say(f"context ready, scratch {ctx.scratch_bytes / 2**30:.1f} GiB")
+            b = sams.Buffers(d, n, r, c, k, w.eps, gs.x1())
+            g = gs.step(0)
+            ctx.amsgrad_ef_update(g, b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+            ctx.sketch_accumulate(b.e_u, b.S_workers)
+            ctx.sketch_reduce(b.S_workers, b.S_mean)
+            ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
+            ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+            torch.cuda.synchronize()
+            say("iteration 1 done")
+            idx1, delta1 = host(b.idx).copy(), host(b.delta).copy()
+            pre = [dict(m=host(b.m[:, a:z].contiguous()), e=host(b.e_u[:, a:z].contiguous()),
+                        v=host(b.v[a:z].contiguous()), vhat=host(b.vhat[a:z].contiguous()),
+                        x=host(b.x[a:z].contiguous())) for a, z in ranges]
+            gs.step(1, out=g)
+            ctx.amsgrad_ef_update(g, b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, k, w.beta1, w.beta2, w.lr)
+            # dense update on both ends of the vector, every worker
+            for (a, z), st in zip(ranges, pre):
+                sel = idx1[(idx1 >= a) & (idx1 < z)] - a
+                dl = delta1[(idx1 >= a) & (idx1 < z)]
+                o.tail(st["e"], st["x"], sel.astype(np.int32), dl, w.lr)
+                mask = np.zeros(z - a, np.uint8)
+                mask[sel] = 1
+                o.head(host(g[:, a:z].contiguous()), st["m"], st["e"], st["v"], st["vhat"], mask, w.beta1, w.beta2)
+                for key, t in (("m", b.m), ("e", b.e_u)):
+                    assert np.array_equal(host(t[:, a:z].contiguous()), st[key]), (key, a)
+                for key, t in (("v", b.v), ("vhat", b.vhat), ("x", b.x)):
+                    assert np.array_equal(host(t[a:z].contiguous()), st[key]), (key, a)
+            say("dense update checked on both ends")
+            del g, pre
+            # stage 1: two whole (worker, row) tables, bit for bit
+            ctx.sketch_accumulate(b.e_u, b.S_workers)
+            for i, j in ((0, 0), (n - 1, r - 1)):
+                want = o.sketch(host(b.e_u[i]), hp[j:j + 1], c)[0]
+                assert np.array_equal(host(b.S_workers[i, j]), want), ("sketch", i, j)
+                say(f"table of worker {i}, row {j} checked")
+            # stage 2
+            ctx.sketch_reduce(b.S_workers, b.S_mean)
+            S_mean = host(b.S_mean)
+            assert np.array_equal(S_mean, o.sketch_mean(host(b.S_workers)))
+            # stage 3: estimates on both ends, index set by its properties
+            est_g = torch.empty(d, device="cuda")
+            ctx.unsketch_estimates(b.S_mean, b.vhat, est_g)
+            for a, z in ranges:
+                want = o.unsketch(S_mean, host(b.vhat[a:z].contiguous()), z - a, hp, l0=a)
+                assert np.array_equal(host(est_g[a:z].contiguous()), want), ("est", a)
+            say("estimates checked on both ends")
+            ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
+            idx = host(b.idx).copy()
+            est = host(est_g)
+            del est_g
+            check_topk_properties(est, idx, k)
+            del est
+            say("index set checked")
+            # stage 4 on the compacted columns (same arithmetic, the oracle only ever reads u[:, idx])
+            ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+            il = torch.from_numpy(idx.astype(np.int64)).cuda()
+            u_c = host(b.e_u[:, il].contiguous())
+            vh_c = host(b.vhat[il].contiguous())
+            U_w, delta = o.gather(u_c, vh_c, np.arange(k, dtype=np.int32))
+            assert np.array_equal(host(b.U_workers), U_w) and np.array_equal(host(b.delta), delta)
+            # stage 5, tail only, on the selected coordinates
+            x_c = host(b.x[il].contiguous())
+            ctx.amsgrad_ef_update(None, b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, k, w.beta1, w.beta2, w.lr)
+            o.tail(u_c, x_c, np.arange(k, dtype=np.int32), delta, w.lr)
+            assert np.array_equal(host(b.x[il].contiguous()), x_c)
+            assert not host(b.e_u[:, il].contiguous()).any()
+            say("gather and tail checked")
+    finally:
+        for key, val in dict(fuse_head=0, stage_rows=0, run_pad=32).items():
+            sams.sams_configure(key, val)
