@@ -83,6 +83,8 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "stage_rows"  0..16 (default 0 = all r rows): rows of the sketch staged at once on the binned path; the
  *                 staging buffer holds 4*n*stage_rows*(1.1 to 1.5)*d bytes and stage 1 runs row group after
  *                 row group (each group after the first re-reads u)
+ *   "fuse_median" 1 (default) or 0: with 1 and r <= 6 the plan-driven recovery keeps the row estimates in
+ *                 registers; with 0 they go through a [r][d] scratch array
  *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
  *                 1: one gather per (row, coordinate) straight from the table
  *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)

@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {14, 15, 11, 1024, 0, 1024, 0, 0, 0, 32};
+Tunables g_tun = {14, 15, 11, 1024, 0, 1024, 0, 0, 1, 0, 32};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -175,6 +175,9 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "fuse_head")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.fuse_head = value;
+    } else if (!strcmp(key, "fuse_median")) {
+        if (value < 0 || value > 1) return SAMS_EINVAL;
+        g_tun.fuse_median = value;
     } else if (!strcmp(key, "stage_rows")) {
         if (value < 0 || value > SAMS_MAX_ROWS) return SAMS_EINVAL;
         g_tun.stage_rows = value;

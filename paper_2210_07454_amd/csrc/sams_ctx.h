@@ -83,6 +83,7 @@ struct Tunables {
     int scatter_threads;  // workgroup size of the scatter kernel
     int estimate_path;    // 0 = stage 3 through the plan when there is one, 1 = direct gathers from the table
     int fuse_head;        // 1 = amsgrad_ef_update also stages u for the next sketch_accumulate
+    int fuse_median;      // 1 = recovery keeps the row estimates in registers (r <= 6), 0 = through memory
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats
     int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
 };
@@ -150,6 +151,24 @@ struct ProfScope {
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, (ctx)->stream, __VA_ARGS__);      \
     } while (0)
 
+// median of R row estimates (Sec. II-C); for an even R the lower middle element
+template <int R>
+__device__ __forceinline__ float median_of(float (&a)[R])
+{
+    // odd-even transposition network: R rounds sort R values; compile-time unrolled
+#pragma unroll
+    for (int round = 0; round < R; ++round) {
+#pragma unroll
+        for (int p = (round & 1); p + 1 < R; p += 2) {
+            float lo = a[p + 1] < a[p] ? a[p + 1] : a[p];
+            float hi = a[p + 1] < a[p] ? a[p] : a[p + 1];
+            a[p] = lo;
+            a[p + 1] = hi;
+        }
+    }
+    return a[(R - 1) / 2];
+}
+
 // ---- enqueue functions (all asynchronous on ctx->stream; return SAMS_OK or SAMS_EHIP) ----
 int enqueue_fill_u32(sams_ctx *ctx, uint32_t *p, int64_t n, uint32_t val);
 int enqueue_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
@@ -168,6 +187,8 @@ int plan_create(sams_ctx *ctx, const Tunables &tun);
 void plan_destroy(sams_ctx *ctx);
 int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers);
 int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *rowest);
+// whole recovery through the plan when the fused collect+median kernel applies; *done says whether it ran
+int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done);
 bool head_can_fuse(const sams_ctx *ctx);
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
                          float beta1, float beta2, float rho);

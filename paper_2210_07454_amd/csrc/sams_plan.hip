@@ -34,6 +34,8 @@ constexpr int kPlanThreads = 1024;
 constexpr int kScatterThreads = 256;
 constexpr int kNumXcd = 8;
 constexpr int kAccDepth = 4;                // chunks in flight per workgroup of the accumulate kernel
+constexpr int kFusedThreads = 1024;          // kernels whose threads own the same 4-coordinate groups throughout
+constexpr int kFusedIters = 4;              // tiles of at most 2^14 coordinates = 4 float4 per thread
 constexpr int kRunPad = 16;                 // slot-group granularity in elements (64 bytes); runs are padded to a multiple of it
 
 constexpr uint16_t kSrcPad = 0x7fffu;          // slot source meaning "padding": tiles hold at most 2^14 coordinates
@@ -343,8 +345,6 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
 // needs in LDS is produced on the spot from g, m and e, so u is never read back from memory.  The
 // arithmetic is the same, operation for operation, as in the separate head kernel.  1024 threads, each
 // owning the same 4-coordinate groups for every worker so that the worker sum of g stays in registers.
-constexpr int kFusedThreads = 1024;
-constexpr int kFusedIters = 4;      // tiles of at most 2^14 coordinates = 4 float4 per thread
 
 struct HeadArgs {
     const float *g;
@@ -603,6 +603,102 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
     }
 }
 
+// k_bin_collect with the median of Sec. II-C and the 1/sqrt(vhat) scaling of Alg. 3 fused in: each thread
+// keeps the R row estimates of its 16 coordinates in registers, so the per-row estimates never go to memory.
+template <int R>
+__global__ void __launch_bounds__(kFusedThreads)
+k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ srcp,
+                     const uint32_t *__restrict__ dst16, const uint32_t *__restrict__ pbase,
+                     const float *__restrict__ vhat, float *__restrict__ est, int64_t d, int tile_log2,
+                     int64_t ntile, int64_t rowlen)
+{
+    extern __shared__ float rowbuf[];                                // [2][L]
+    const int L = 1 << tile_log2;
+    const int64_t tile = blockIdx.x;
+    const int64_t l0 = tile << tile_log2;
+    float a[R][kFusedIters][4];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        float *buf = rowbuf + (j & 1) * L;
+        const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
+        const uint16_t *sj = srcp + (int64_t)j * rowlen;
+        const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+        const float *lj = lk + (int64_t)j * rowlen;
+        for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
+            const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
+            const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+            const float4 v = load_stream(reinterpret_cast<const float4 *>(lj + at));
+            const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
+                           s3 = packed.y >> 16;
+            if (s0 != kSrcPad) buf[s0 & 0x7fffu] = (s0 & 0x8000u) ? -v.x : v.x;
+            if (s1 != kSrcPad) buf[s1 & 0x7fffu] = (s1 & 0x8000u) ? -v.y : v.y;
+            if (s2 != kSrcPad) buf[s2 & 0x7fffu] = (s2 & 0x8000u) ? -v.z : v.z;
+            if (s3 != kSrcPad) buf[s3 & 0x7fffu] = (s3 & 0x8000u) ? -v.w : v.w;
+        }
+        __syncthreads();   // the other buffer is free again once every thread has passed this barrier
+#pragma unroll
+        for (int it = 0; it < kFusedIters; ++it) {
+            const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p < L) q = *reinterpret_cast<const float4 *>(buf + p);
+            a[j][it][0] = q.x; a[j][it][1] = q.y; a[j][it][2] = q.z; a[j][it][3] = q.w;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < kFusedIters; ++it) {
+        const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+        if (p < L && l0 + p < d) {
+            float vh[4] = {1.f, 1.f, 1.f, 1.f};
+            if (vhat) {
+                const float4 q = *reinterpret_cast<const float4 *>(vhat + l0 + p);
+                vh[0] = q.x; vh[1] = q.y; vh[2] = q.z; vh[3] = q.w;
+            }
+            float o[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float col[R];
+#pragma unroll
+                for (int j = 0; j < R; ++j) col[j] = a[j][it][t];
+                const float med = median_of<R>(col);
+                o[t] = vhat ? (med / sqrtf(vh[t])) : med;
+            }
+            *reinterpret_cast<float4 *>(est + l0 + p) = make_float4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+constexpr int kFusedMedianMaxRows = 6;      // R * 16 row estimates per thread must stay in registers
+
+int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done)
+{
+    Plan &pl = ctx->plan;
+    *done = false;
+    if (ctx->r > kFusedMedianMaxRows || (ctx->d & 3) != 0 || (int64_t)ctx->n * pl.stage_rows < ctx->r) return SAMS_OK;
+    const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
+    float *lk = pl.stg;
+    {
+        ProfScope ps(ctx, KID_BIN_LOOKUP);
+        hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)pl.nbins, (unsigned)ctx->r), dim3(1024), (size_t)(W * 4),
+                           ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2, pl.nbins, pl.rowlen, 0);
+    }
+    {
+        ProfScope ps(ctx, KID_BIN_COLLECT);
+#define SAMS_CM(RR)                                                                                       \
+    case RR:                                                                                              \
+        hipLaunchKernelGGL(k_bin_collect_median<RR>, dim3((unsigned)pl.ntile), dim3(kFusedThreads),       \
+                           (size_t)(2 * L * 4), ctx->stream, lk, pl.srcp, pl.dst16, pl.pbase, vhat, est,   \
+                           ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);                                     \
+        break;
+        switch (ctx->r) {
+            SAMS_CM(1) SAMS_CM(2) SAMS_CM(3) SAMS_CM(4) SAMS_CM(5) SAMS_CM(6)
+        }
+#undef SAMS_CM
+    }
+    SAMS_HIP(hipGetLastError());
+    *done = true;
+    return SAMS_OK;
+}
+
 int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *rowest)
 {
     Plan &pl = ctx->plan;
@@ -747,6 +843,12 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(CH * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+#define SAMS_CM(RR)                                                                                \
+    if (e == hipSuccess)                                                                           \
+        e = hipFuncSetAttribute((const void *)k_bin_collect_median<RR>,                            \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
+        SAMS_CM(1) SAMS_CM(2) SAMS_CM(3) SAMS_CM(4) SAMS_CM(5) SAMS_CM(6)
+#undef SAMS_CM
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(W * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((NB + 1) * 4));

@@ -13,23 +13,6 @@ namespace sams {
 // stage 3a: per-coordinate estimates (Sec. II-C median, Alg. 3 scaling)
 // ------------------------------------------------------------------------------------------
 template <int R>
-__device__ __forceinline__ float median_of(float (&a)[R])
-{
-    // odd-even transposition network: R rounds sort R values; compile-time unrolled
-#pragma unroll
-    for (int round = 0; round < R; ++round) {
-#pragma unroll
-        for (int p = (round & 1); p + 1 < R; p += 2) {
-            float lo = a[p + 1] < a[p] ? a[p + 1] : a[p];
-            float hi = a[p + 1] < a[p] ? a[p] : a[p + 1];
-            a[p] = lo;
-            a[p + 1] = hi;
-        }
-    }
-    return a[(R - 1) / 2];
-}
-
-template <int R>
 __global__ void __launch_bounds__(256)
 k_estimate(const float *__restrict__ S, const float *__restrict__ vhat, float *__restrict__ est,
            HashParams hp, int64_t d, int64_t c)
@@ -244,6 +227,9 @@ int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, floa
     const int block = 256;
     const int grid = grid_for(ctx->d, block);
     if (ctx->plan.mode == PLAN_BINNED && g_tun.estimate_path == 0) {
+        bool done = false;
+        if (g_tun.fuse_median) SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done));
+        if (done) return SAMS_OK;
         SAMS_TRY(enqueue_row_estimates_planned(ctx, S_mean, ctx->plan.rowest));
         switch (ctx->r) {
 #define SAMS_CASE(R)                                                                                  \
