@@ -27,7 +27,7 @@ extern int g_last_hip_error;
     } while (0)
 
 constexpr int kWave = 64;
-constexpr int kSelTile = 2048;      // coordinates one wavefront compacts in the selection
+constexpr int kSelTile = 8192;      // coordinates one wavefront compacts in the selection
 constexpr int kHistBins = 2048;     // first radix digit: 11 bits, then 10 and 10
 constexpr int kSelPasses = 3;
 

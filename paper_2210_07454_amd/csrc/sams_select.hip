@@ -86,29 +86,48 @@ k_sel_hist(const float *__restrict__ est, int64_t d, int pass, const SelState *_
         if (lh[t]) atomicAdd(&hist[t], lh[t]);
 }
 
-// choose the digit in which the k_rem-th largest key lies; clear the histogram for the next pass
-__global__ void k_sel_pick(SelState *st, uint32_t *hist, int pass)
+// exclusive prefix sum over the 1024 threads of a block (part: 1024 words of LDS)
+__device__ __forceinline__ uint32_t block_exclusive_scan_1024(uint32_t val, uint32_t *part)
 {
-    __shared__ uint32_t lh[kHistBins];
-    const int nb = 1 << sel_width(pass);
-    for (int t = threadIdx.x; t < kHistBins; t += blockDim.x) {
-        lh[t] = hist[t];
-        hist[t] = 0;
-    }
+    const int t = threadIdx.x;
+    part[t] = val;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t k_rem = st->k_rem, cum = 0;
-        int b = nb - 1;
-        for (; b > 0; --b) {
-            if (cum + lh[b] >= k_rem) break;
-            cum += lh[b];
-        }
-        uint32_t prefix = (st->prefix << sel_width(pass)) | (uint32_t)b;
+    for (int off = 1; off < 1024; off <<= 1) {
+        const uint32_t x = t >= off ? part[t - off] : 0u;
+        __syncthreads();
+        part[t] += x;
+        __syncthreads();
+    }
+    const uint32_t excl = part[t] - val;
+    __syncthreads();
+    return excl;
+}
+
+// choose the digit in which the k_rem-th largest key lies; clear the histogram for the next pass.
+// 1024 threads; thread t looks at the two bins 2t and 2t+1 counted from the top.
+__global__ void __launch_bounds__(1024)
+k_sel_pick(SelState *st, uint32_t *hist, int pass)
+{
+    __shared__ uint32_t part[1024];
+    const int nb = 1 << sel_width(pass);
+    const int t = threadIdx.x;
+    const int b0 = nb - 1 - 2 * t, b1 = nb - 2 - 2 * t;             // descending bins
+    const uint32_t v0 = b0 >= 0 ? hist[b0] : 0u, v1 = b1 >= 0 ? hist[b1] : 0u;
+    const uint32_t k_rem = st->k_rem, prefix_in = st->prefix;
+    const uint32_t above0 = block_exclusive_scan_1024(v0 + v1, part), above1 = above0 + v0;
+    hist[2 * t] = 0;
+    hist[2 * t + 1] = 0;
+    int b = -1;
+    uint32_t above = 0;
+    if (b0 >= 0 && above0 < k_rem && k_rem <= above0 + v0) { b = b0; above = above0; }
+    if (b1 >= 0 && above1 < k_rem && k_rem <= above1 + v1) { b = b1; above = above1; }
+    if (b >= 0) {                                                    // exactly one thread, since k_rem <= total
+        const uint32_t prefix = (prefix_in << sel_width(pass)) | (uint32_t)b;
         st->prefix = prefix;
-        st->k_rem = k_rem - cum;
+        st->k_rem = k_rem - above;
         if (pass == kSelPasses - 1) {
             st->tau = prefix;
-            st->k_eq = k_rem - cum;
+            st->k_eq = k_rem - above;
         }
     }
 }
@@ -146,45 +165,28 @@ k_sel_scan(const uint32_t *__restrict__ cnt_gt, const uint32_t *__restrict__ cnt
            uint32_t *__restrict__ eq_base)
 {
     __shared__ uint32_t part[1024];
-    const int T = blockDim.x, t = threadIdx.x;
-    const int64_t per = (ntile + T - 1) / T;
-    const int64_t lo = (int64_t)t * per, hi = lo + per < ntile ? lo + per : ntile;
+    const int t = threadIdx.x;
     const uint32_t k_eq = st->k_eq;
-    // pass A: equal counts
-    uint32_t s = 0;
-    for (int64_t q = lo; q < hi; ++q) s += cnt_eq[q];
-    part[t] = s;
-    __syncthreads();
-    if (t == 0) {
-        uint32_t run = 0;
-        for (int q = 0; q < T; ++q) { uint32_t x = part[q]; part[q] = run; run += x; }
-    }
-    __syncthreads();
-    uint32_t run = part[t];
-    __syncthreads();
-    uint32_t s2 = 0;
-    for (int64_t q = lo; q < hi; ++q) {
-        eq_base[q] = run;
-        uint32_t want = run < k_eq ? k_eq - run : 0u;
-        uint32_t ce = cnt_eq[q];
-        s2 += cnt_gt[q] + (ce < want ? ce : want);
-        run += ce;
-    }
-    // pass B: selected counts
-    part[t] = s2;
-    __syncthreads();
-    if (t == 0) {
-        uint32_t r2 = 0;
-        for (int q = 0; q < T; ++q) { uint32_t x = part[q]; part[q] = r2; r2 += x; }
-    }
-    __syncthreads();
-    uint32_t run2 = part[t];
-    for (int64_t q = lo; q < hi; ++q) {
-        sel_base[q] = run2;
-        uint32_t eb = eq_base[q];
-        uint32_t want = eb < k_eq ? k_eq - eb : 0u;
-        uint32_t ce = cnt_eq[q];
-        run2 += cnt_gt[q] + (ce < want ? ce : want);
+    uint32_t eq_run = 0, sel_run = 0;                                // totals of the rounds already done
+    for (int64_t q0 = 0; q0 < ntile; q0 += 1024) {                   // 1024 consecutive tiles per round
+        const int64_t q = q0 + t;
+        const uint32_t ce = q < ntile ? cnt_eq[q] : 0u, cg = q < ntile ? cnt_gt[q] : 0u;
+        const uint32_t eb = eq_run + block_exclusive_scan_1024(ce, part);
+        const uint32_t want = eb < k_eq ? k_eq - eb : 0u;
+        const uint32_t take = cg + (ce < want ? ce : want);
+        const uint32_t sb = sel_run + block_exclusive_scan_1024(take, part);
+        if (q < ntile) {
+            eq_base[q] = eb;
+            sel_base[q] = sb;
+        }
+        if (t == 1023) {
+            part[0] = eb + ce;
+            part[1] = sb + take;
+        }
+        __syncthreads();
+        eq_run = part[0];
+        sel_run = part[1];
+        __syncthreads();
     }
 }
 
@@ -273,7 +275,7 @@ int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel
     for (int pass = 0; pass < kSelPasses; ++pass) {
         SAMS_LAUNCH(ctx, KID_SEL_HIST, k_sel_hist, grid_for(d, 256 * 16, 4096), 256, est, d, pass,
                     ctx->sel, ctx->hist);
-        SAMS_LAUNCH(ctx, KID_SEL_PICK, k_sel_pick, 1, 256, ctx->sel, ctx->hist, pass);
+        SAMS_LAUNCH(ctx, KID_SEL_PICK, k_sel_pick, 1, 1024, ctx->sel, ctx->hist, pass);
     }
     const int waves_per_block = 256 / kWave;
     const int tgrid = (int)((nt + waves_per_block - 1) / waves_per_block);
