@@ -66,11 +66,12 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
  *   "tile_log2"   6..14 (default 14): log2 of the coordinates per tile of the binned sketch path
- *   "win_log2"    4..15 (default 15): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
- *                 accumulated row by row in LDS, larger ones through the binned path
- *   "chunk_log2"  6..11 (default 11): log2 of the stream positions the binned accumulation handles
+ *   "win_log2"    0 or 4..15 (default 0): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
+ *                 accumulated row by row in LDS, larger ones through the binned path.  0 = chosen from n, r, c:
+ *                 2^15, or less (down to 2^12) when that is needed to give the chip enough windows to work on
+ *   "chunk_log2"  0 or 6..11 (default 0 = 11 for 2^15 windows, else 10): log2 of the stream positions the binned accumulation handles
  *                 between two barriers
- *   "acc_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned accumulation; must not
+ *   "acc_threads" 0, 256, 512 or 1024 (default 0 = 1024 for 2^15 windows, else 512): workgroup size of the binned accumulation; must not
  *                 exceed 2^chunk_log2, and a window plus two chunks of 8 bytes must fit in 160 KiB of LDS
  *                 (otherwise sams_create returns SAMS_EINVAL)
  *   "run_pad"     16 or 32 (default 32): stream positions a (tile, window) run is padded to, so that the
@@ -94,6 +95,10 @@ int sams_configure(const char *key, int value);
 
 /* Waits for the context's stream, frees its scratch and the context.  NULL is a no-op. */
 int sams_destroy(sams_ctx *ctx);
+
+/* How this context carries out sketch_accumulate: 0 = one global atomic add per term, 1 = row by row in LDS
+ * (c fits one window), 2 = the binned, order-preserving path.  -1 for a NULL context. */
+int sams_sketch_mode(const sams_ctx *ctx);
 
 /* Device bytes the context allocated. */
 int64_t sams_scratch_bytes(const sams_ctx *ctx);

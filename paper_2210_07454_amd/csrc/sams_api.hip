@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {14, 15, 11, 1024, 0, 1024, 0, 0, 1, 0, 32};
+Tunables g_tun = {14, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 32};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -158,13 +158,13 @@ int sams_configure(const char *key, int value)
         if (value < 6 || value > 14) return SAMS_EINVAL;
         g_tun.tile_log2 = value;
     } else if (!strcmp(key, "win_log2")) {
-        if (value < 4 || value > 15) return SAMS_EINVAL;
+        if (value != 0 && (value < 4 || value > 15)) return SAMS_EINVAL;
         g_tun.win_log2 = value;
     } else if (!strcmp(key, "chunk_log2")) {
-        if (value < 6 || value > 11) return SAMS_EINVAL;
+        if (value != 0 && (value < 6 || value > 11)) return SAMS_EINVAL;
         g_tun.chunk_log2 = value;
     } else if (!strcmp(key, "acc_threads")) {
-        if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
+        if (value != 0 && value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
         g_tun.acc_threads = value;
     } else if (!strcmp(key, "scatter_threads")) {
         if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
@@ -192,6 +192,8 @@ int sams_configure(const char *key, int value)
     }
     return SAMS_OK;
 }
+
+int sams_sketch_mode(const sams_ctx *ctx) { return ctx ? ctx->plan.mode : -1; }
 
 int64_t sams_scratch_bytes(const sams_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }
 

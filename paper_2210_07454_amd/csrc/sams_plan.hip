@@ -36,6 +36,7 @@ constexpr int kNumXcd = 8;
 constexpr int kAccDepth = 4;                // chunks in flight per workgroup of the accumulate kernel
 constexpr int kFusedThreads = 1024;          // kernels whose threads own the same 4-coordinate groups throughout
 constexpr int kFusedIters = 4;              // tiles of at most 2^14 coordinates = 4 float4 per thread
+constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one compute unit; the dynamic-LDS cap of every kernel here
 constexpr int kRunPad = 16;                 // slot-group granularity in elements (64 bytes); runs are padded to a multiple of it
 
 constexpr uint16_t kSrcPad = 0x7fffu;          // slot source meaning "padding": tiles hold at most 2^14 coordinates
@@ -773,7 +774,7 @@ static int launch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_att
     const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * TH * UN * sizeof(uint2);
     if (set_attr) {
         SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate<TH, UN>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
         return SAMS_OK;
     }
     const int64_t groups = (int64_t)rg.rj * pl.nbins;
@@ -802,16 +803,28 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     Plan &pl = ctx->plan;
     pl.win_log2 = tun.win_log2;
     pl.tile_log2 = tun.tile_log2;
-    pl.chunk_log2 = tun.chunk_log2;
-    pl.acc_threads = tun.acc_threads;
+    if (pl.win_log2 == 0) {
+        // automatic window: the largest one (longest runs, least padding) that still leaves about four
+        // accumulate workgroups per compute unit (256 units); never more than the table needs
+        pl.win_log2 = 15;
+        while (pl.win_log2 > 12 &&
+               (int64_t)ctx->n * ctx->r * ((ctx->c + ((int64_t)1 << pl.win_log2) - 1) >> pl.win_log2) < 1024)
+            --pl.win_log2;
+        while (pl.win_log2 < 15 && ((int64_t)1 << pl.win_log2) < ctx->c &&
+               (((int64_t)1 << pl.tile_log2) << pl.win_log2) / ctx->c < 64)
+            ++pl.win_log2;                                           // but keep runs of at least 64 positions
+    }
+    // a 32K window leaves room for one workgroup per unit: 1024 threads, 2048-position chunks; smaller
+    // windows run two or more 512-thread workgroups per unit with 1024-position chunks
+    pl.chunk_log2 = tun.chunk_log2 ? tun.chunk_log2 : (pl.win_log2 >= 15 ? 11 : 10);
+    pl.acc_threads = tun.acc_threads ? tun.acc_threads : (pl.win_log2 >= 15 ? 1024 : 512);
     pl.run_pad = tun.run_pad;
     pl.stage_rows = (tun.stage_rows <= 0 || tun.stage_rows > ctx->r) ? ctx->r : tun.stage_rows;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
     pl.mode = pl.nbins <= 1 ? PLAN_LDS_ROW : PLAN_BINNED;
     if (pl.mode == PLAN_LDS_ROW) {
-        SAMS_HIP(hipFuncSetAttribute((const void *)k_sketch_lds, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)(W * 4)));
+        SAMS_HIP(hipFuncSetAttribute((const void *)k_sketch_lds, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
         return SAMS_OK;
     }
     // sort keys must fit 32 bits; LDS must hold a window plus the chunk exchange buffers
@@ -839,19 +852,19 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     do {
         if (rc != SAMS_OK) break;
         if (!h_total || !h_base || !h_tile) { rc = SAMS_ENOMEM; break; }
-        hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(CH * 4));
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(L * 4));
+        hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
 #define SAMS_CM(RR)                                                                                \
     if (e == hipSuccess)                                                                           \
         e = hipFuncSetAttribute((const void *)k_bin_collect_median<RR>,                            \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         SAMS_CM(1) SAMS_CM(2) SAMS_CM(3) SAMS_CM(4) SAMS_CM(5) SAMS_CM(6)
 #undef SAMS_CM
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(W * 4));
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * L * 4));
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((NB + 1) * 4));
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         rc = dispatch_acc(ctx, nullptr, RowGroup{0, 0, 0, 0}, true);
         if (rc != SAMS_OK) break;

@@ -26,7 +26,7 @@ def sams():
 
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
-    "default": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32, scatter_threads=1024,
+    "default": dict(tile_log2=14, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=32, scatter_threads=1024,
                     sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1),
     "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=16,
                                  scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1),
@@ -145,9 +145,9 @@ def test_sketch_accumulate_float_within_tolerance(sams, path, wl, d):
         ctx.sketch_accumulate(u, S)
         got32 = host(S)
         got = got32.astype(np.float64)
+        binned = ctx.sketch_mode == 2
     assert np.all(np.abs(got - want) <= TOL * A + 1e-37)
-    cfg = PATHS[path]
-    if cfg["sketch_path"] == 0 and w.c > (1 << cfg["win_log2"]):
+    if binned:
         # binned path: terms are added in ascending coordinate order, exactly like the oracle's loop
         o32 = Oracle("f32")
         assert np.array_equal(got32, np.stack([o32.sketch(uh[i], hp, w.c) for i in range(w.n)]))
