@@ -31,17 +31,28 @@ def build(force: bool = False) -> str:
     return _SO
 
 
+def _declare(l: ctypes.CDLL) -> ctypes.CDLL:
+    l.orc_hash_y.restype = ctypes.c_uint32
+    l.orc_hash_y.argtypes = [ctypes.c_uint32] * 3
+    l.orc_bucket.restype = ctypes.c_int64
+    l.orc_bucket.argtypes = [ctypes.c_uint32] * 3 + [ctypes.c_int64]
+    l.orc_sign.restype = ctypes.c_int
+    l.orc_sign.argtypes = [ctypes.c_uint32] * 3
+    return l
+
+
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
-        _lib.orc_hash_y.restype = ctypes.c_uint32
-        _lib.orc_hash_y.argtypes = [ctypes.c_uint32] * 3
-        _lib.orc_bucket.restype = ctypes.c_int64
-        _lib.orc_bucket.argtypes = [ctypes.c_uint32] * 3 + [ctypes.c_int64]
-        _lib.orc_sign.restype = ctypes.c_int
-        _lib.orc_sign.argtypes = [ctypes.c_uint32] * 3
+        _lib = _declare(ctypes.CDLL(build()))
     return _lib
+
+
+def use_library(path: str | None) -> None:
+    """Tests only: route every later call to another build of the oracle (a deliberately broken copy,
+    to show that the pins notice); ``None`` goes back to the real one."""
+    global _lib
+    _lib = None if path is None else _declare(ctypes.CDLL(path))
 
 
 def _p(a):

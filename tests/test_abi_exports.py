@@ -56,3 +56,23 @@ def test_binding_refuses_to_run_without_a_gpu():
         pytest.skip("GPU present")
     with pytest.raises(RuntimeError):
         sams.Context(100, 1, 5, 8, 1, np.ones((5, 4), dtype=np.uint32))
+
+
+def test_configure_rejects_unknown_keys_and_bad_values_without_a_gpu():
+    from paper_2210_07454_amd import sams
+    lib = sams.load()
+    ok = [(b"tile_log2", 14), (b"win_log2", 0), (b"win_log2", 15), (b"chunk_log2", 0), (b"acc_threads", 0),
+          (b"run_pad", 32), (b"scatter_threads", 1024), (b"sketch_path", 0), (b"estimate_path", 0),
+          (b"fuse_head", 0), (b"fuse_median", 1), (b"stage_rows", 0)]
+    bad = [(b"tile_log2", 15), (b"tile_log2", 5), (b"win_log2", 16), (b"win_log2", 3), (b"chunk_log2", 12),
+           (b"acc_threads", 384), (b"run_pad", 8), (b"scatter_threads", 100), (b"sketch_path", 2),
+           (b"estimate_path", -1), (b"fuse_head", 2), (b"stage_rows", 17), (b"no_such_key", 1)]
+    for key, val in bad:
+        assert lib.sams_configure(key, val) == sams.SAMS_EINVAL, (key, val)
+    assert lib.sams_configure(None, 0) == sams.SAMS_EINVAL
+    for key, val in ok:                      # leaves the defaults in place
+        assert lib.sams_configure(key, val) == sams.SAMS_OK, (key, val)
+    assert lib.sams_sketch_mode(None) == -1
+    assert lib.sams_profile_kernels() > 10
+    names = {lib.sams_profile_name(q).decode() for q in range(lib.sams_profile_kernels())}
+    assert {"k_head_scatter", "k_bin_accumulate", "k_sel_hist"} <= names

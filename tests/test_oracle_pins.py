@@ -345,6 +345,31 @@ def test_lemma3_auxiliary_sequence_and_structural_invariants():
         vh_prev, idx_prev = h["vhat"].copy(), h["idx"].astype(np.int64)
 
 
+def test_lemma3_holds_with_a_decaying_step_size():
+    # With alpha_t changing, Alg. 2 scales the carried error by alpha_{t-1}/alpha_t (worker lines for the sketch
+    # and for e_t); Lemma 3 then reads x_{t+1} - x~_{t+1} = alpha_t vhat_t^{-1/2} e_t.  Fails if the ratio is
+    # dropped, inverted, or applied to m instead of e.
+    o = Oracle("f64")
+    d, n, k, T, r, c = 1500, 3, 40, 12, 5, 96
+    b1, b2, eps, lr0 = 0.9, 0.99, 1e-8, 1e-2
+    rng = np.random.default_rng(17)
+    G = [rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 0, d) for _ in range(T)]
+    x1 = rng.standard_normal(d)
+    hp = inputs.hash_params(r, seed=3)
+    st = o.init_state(x1, n, eps)
+    xt = x1.copy()
+    alpha_prev = None
+    for t in range(1, T + 1):
+        alpha = lr0 / np.sqrt(t)
+        rho = 1.0 if alpha_prev is None else alpha_prev / alpha
+        o.step(np.ascontiguousarray(G[t - 1]), st, hp, c, k, b1, b2, alpha, rho=rho)
+        xt = xt - alpha * st["m"].mean(axis=0) / np.sqrt(st["vhat"])
+        carried = alpha * st["e"].mean(axis=0) / np.sqrt(st["vhat"])
+        gap = st["x"] - xt - carried
+        assert np.abs(gap).max() <= 1e-11 * (np.abs(st["x"]).max() + np.abs(carried).max()), t
+        alpha_prev = alpha
+
+
 def test_plain_unsketch_variant_skips_the_vhat_scaling():
     # Alg. 1 uses the original operator U_0 (no second input): est and Delta carry no 1/sqrt(vhat)
     o = Oracle("f64")
