@@ -864,7 +864,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
 #undef SAMS_CM
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);   // + 1 KiB static
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         rc = dispatch_acc(ctx, nullptr, RowGroup{0, 0, 0, 0}, true);
         if (rc != SAMS_OK) break;
