@@ -33,7 +33,7 @@ namespace sams {
 constexpr int kPlanThreads = 1024;
 constexpr int kScatterThreads = 256;
 constexpr int kNumXcd = 8;
-constexpr int kAccDepth = 4;                // chunks in flight per workgroup of the accumulate kernel
+constexpr int kAccDepth = 8;                // chunks in flight per workgroup of the accumulate kernel
 constexpr int kFusedThreads = 1024;          // kernels whose threads own the same 4-coordinate groups throughout
 constexpr int kFusedIters = 4;              // tiles of at most 2^14 coordinates = 4 float4 per thread
 constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one compute unit; the dynamic-LDS cap of every kernel here
