@@ -77,6 +77,17 @@ WORKLOADS = {
     "C5": Workload("C5-stress", d=1_300_000_000, n=4, r=5, c=16_777_216, k=1_300_000, steps=3,
                    noise="normal", nseg=1, lo=-3.0, hi=-3.0, heavy="pareto", heavy_frac=0.001,
                    heavy_alpha=1.2),
+    # The sketch shapes of the paper's own experiments (Sec. V): ResNet-50 ("about 25M parameters", 16 workers,
+    # 10 rows x 100,000 columns, k = 50,000) and LeNet-5 ("about 60k parameters", 50 and 100 workers, 5 rows x
+    # 400 columns, k = 500).  Even row count, column counts that are not powers of two.  The gradient recipe is
+    # synthetic as above (the paper's come from CIFAR / MNIST training).
+    "P1": Workload("P1-paper-resnet50", d=25_000_000, n=16, r=10, c=100_000, k=50_000, steps=5,
+                   noise="student3", nseg=100, lo=-5.0, hi=-1.0, heavy="uniform", heavy_frac=0.005,
+                   heavy_scale=10.0),
+    "P2a": Workload("P2-paper-lenet5-n50", d=60_000, n=50, r=5, c=400, k=500, steps=10, noise="normal",
+                    nseg=8, lo=-3.0, hi=-1.0, heavy="uniform", heavy_count=100, heavy_abs=True),
+    "P2b": Workload("P2-paper-lenet5-n100", d=60_000, n=100, r=5, c=400, k=500, steps=10, noise="normal",
+                    nseg=8, lo=-3.0, hi=-1.0, heavy="uniform", heavy_count=100, heavy_abs=True),
 }
 
 

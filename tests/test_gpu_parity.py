@@ -268,7 +268,8 @@ def near_threshold(est, k, idx_a, idx_b):
 
 
 @pytest.mark.parametrize("wl,d,steps", [("C1", 65_536, 10), ("C2", 400_000, 6), ("C3", 300_000, 5),
-                                        ("C4", 600_000, 5), ("C5", 500_000, 3)])
+                                        ("C4", 600_000, 5), ("C5", 500_000, 3), ("P1", 500_000, 3),
+                                        ("P2a", 60_000, 4), ("P2b", 60_000, 3)])
 def test_chained_steps_follow_the_oracle(sams, path, wl, d, steps):
     """Free-running GPU run; at every step the oracle is restarted from the GPU's previous state, so
     each step is compared on real evolving state (bitmap of I_{t-1}, error feedback, vhat)."""
