@@ -178,6 +178,19 @@ int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t 
                 float *delta);
 
 /*
+ * Second round with over-selection (Sec. III-A: "select the largest Pk coordinates to extract their exact
+ * values ... finally select the top-k coordinates among these Pk").  For a context created with k = P*k_out:
+ * after unsketch_topk (P*k_out candidates) and gather_topk (their exact averaged values), keep the k_out
+ * candidates with the largest |delta_in|, ties going to the smaller coordinate, in ascending coordinate order.
+ *   idx_in   [k] int32 in, ascending (unsketch_topk's output)     delta_in  [k] in (gather_topk's output)
+ *   k_out    1 <= k_out <= k
+ *   idx_out  [k_out] int32 out      delta_out [k_out] out
+ * The results feed amsgrad_ef_update with k_sel = k_out.  Uses the context's estimate scratch.
+ */
+int topk_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_out, int32_t *idx_out,
+                float *delta_out);
+
+/*
  * Stage 5 -- AMSGrad update with error feedback (Alg. 2).  One call finishes iteration t and starts
  * iteration t+1:
  *   finish t ("tail"; lines for e_t and x_{t+1}; e_t is zero on I_t as the proof of Lemma 3 states),

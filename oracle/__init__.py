@@ -151,6 +151,19 @@ class Oracle:
                                ctypes.c_int64(d), _p(U_w), _p(delta))
         return U_w, delta
 
+    def refine(self, idx_in, delta_in, k_out):
+        self._chk(delta_in)
+        idx_in = np.ascontiguousarray(idx_in, dtype=np.int32)
+        idx_out = np.empty(k_out, dtype=np.int32)
+        delta_out = np.empty(k_out, dtype=self.dtype)
+        fn = self._fn("orc_refine")
+        fn.restype = ctypes.c_int
+        rc = fn(_p(idx_in), _p(delta_in), ctypes.c_int64(idx_in.shape[0]), ctypes.c_int64(k_out), _p(idx_out),
+                _p(delta_out))
+        if rc != 0:
+            raise MemoryError("orc_refine")
+        return idx_out, delta_out
+
     def head(self, g, m, e_u, v, vhat, in_prev, beta1, beta2, rho=1.0):
         """In place on m, e_u (receives u), v, vhat."""
         self._chk(g, m, e_u, v, vhat)

@@ -126,6 +126,22 @@ int FN(orc_topk)(const REAL *est, int64_t d, int64_t k, int32_t *idx /* [k] */)
     return 0;
 }
 
+/* Sec. III-A, over-selection: among k_in candidates (ascending coordinates idx_in with their exact averaged
+ * values delta_in) keep the k_out with the largest magnitude, ties to the smaller coordinate, ascending. */
+int FN(orc_refine)(const int32_t *idx_in, const REAL *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out,
+                   REAL *delta_out)
+{
+    int32_t *pos = (int32_t *)malloc((size_t)k_out * sizeof(int32_t));
+    if (!pos) return -1;
+    if (FN(orc_topk)(delta_in, k_in, k_out, pos) != 0) { free(pos); return -1; }
+    for (int64_t q = 0; q < k_out; ++q) {
+        idx_out[q] = idx_in[pos[q]];
+        delta_out[q] = delta_in[pos[q]];
+    }
+    free(pos);
+    return 0;
+}
+
 /* Second round (Sec. III-A) and the definition of Delta_t^(i) under Alg. 2:
  * U^(i)[q] = u^(i)[idx[q]];  Delta[q] = ((sum_i U^(i)[q]) / n) / sqrt(vhat[idx[q]]). */
 void FN(orc_gather)(const REAL *u /* [n][d] */, const REAL *vhat /* [d] or NULL */,

@@ -15,7 +15,7 @@ static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
     "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds", "k_bin_lookup",
-    "k_bin_collect", "k_est_median", "k_head_scatter"};
+    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -261,7 +261,15 @@ int unsketch_topk(sams_ctx *ctx, const float *S_mean, const float *vhat, int32_t
         !aligned16(est_sel))
         return SAMS_EINVAL;
     SAMS_TRY(enqueue_estimate(ctx, S_mean, vhat, ctx->est));
-    return enqueue_select(ctx, ctx->est, idx, est_sel);
+    return enqueue_select(ctx, ctx->est, ctx->d, ctx->k, idx, est_sel);
+}
+
+int topk_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_out, int32_t *idx_out,
+                float *delta_out)
+{
+    if (!ctx || !idx_in || !delta_in || !idx_out || !delta_out || k_out < 1 || k_out > ctx->k) return SAMS_EINVAL;
+    if (!aligned16(idx_in) || !aligned16(delta_in) || !aligned16(idx_out) || !aligned16(delta_out)) return SAMS_EINVAL;
+    return enqueue_refine(ctx, idx_in, delta_in, ctx->k, k_out, idx_out, delta_out);
 }
 
 int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx, float *U_workers,

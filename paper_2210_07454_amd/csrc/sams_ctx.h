@@ -44,7 +44,7 @@ enum KernelId {
     KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
     KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
     KID_GATHER, KID_PLAN_BUILD, KID_BIN_SCATTER, KID_BIN_ACCUMULATE, KID_SKETCH_LDS, KID_BIN_LOOKUP,
-    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_COUNT
+    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_COUNT
 };
 const char *kernel_name(int kid);
 
@@ -194,6 +194,8 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                          float beta1, float beta2, float rho);
 // sams_select.hip
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
-int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel);
+int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel);
+int enqueue_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_in, int64_t k_out,
+                   int32_t *idx_out, float *delta_out);
 
 }  // namespace sams

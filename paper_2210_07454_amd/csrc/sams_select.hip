@@ -266,23 +266,43 @@ int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, floa
     return SAMS_OK;
 }
 
-int enqueue_select(sams_ctx *ctx, const float *est, int32_t *idx, float *est_sel)
+// idx_out[q] = idx_in[pos[q]]: positions among the candidates back to coordinates
+__global__ void __launch_bounds__(256)
+k_refine_map(const int32_t *__restrict__ idx_in, const int32_t *__restrict__ pos, int64_t k_out,
+             int32_t *__restrict__ idx_out)
 {
-    const int64_t d = ctx->d, nt = ctx->ntile;
-    uint32_t *cnt_gt = ctx->cnt, *cnt_eq = ctx->cnt + nt;
-    uint32_t *sel_base = ctx->base, *eq_base = ctx->base + nt;
-    SAMS_LAUNCH(ctx, KID_SEL_INIT, k_sel_init, 1, 256, ctx->sel, (uint32_t)ctx->k, ctx->hist);
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q < k_out) idx_out[q] = idx_in[pos[q]];
+}
+
+// the k entries of keys[0..len) with the largest magnitude, ties to the smaller position; positions ascending
+int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel)
+{
+    const int64_t nt = (len + kSelTile - 1) / kSelTile;               // <= ctx->ntile since len <= d
+    uint32_t *cnt_gt = ctx->cnt, *cnt_eq = ctx->cnt + ctx->ntile;
+    uint32_t *sel_base = ctx->base, *eq_base = ctx->base + ctx->ntile;
+    SAMS_LAUNCH(ctx, KID_SEL_INIT, k_sel_init, 1, 256, ctx->sel, (uint32_t)k, ctx->hist);
     for (int pass = 0; pass < kSelPasses; ++pass) {
-        SAMS_LAUNCH(ctx, KID_SEL_HIST, k_sel_hist, grid_for(d, 256 * 16, 4096), 256, est, d, pass,
+        SAMS_LAUNCH(ctx, KID_SEL_HIST, k_sel_hist, grid_for(len, 256 * 16, 4096), 256, keys, len, pass,
                     ctx->sel, ctx->hist);
         SAMS_LAUNCH(ctx, KID_SEL_PICK, k_sel_pick, 1, 1024, ctx->sel, ctx->hist, pass);
     }
     const int waves_per_block = 256 / kWave;
     const int tgrid = (int)((nt + waves_per_block - 1) / waves_per_block);
-    SAMS_LAUNCH(ctx, KID_SEL_COUNT, k_sel_count, tgrid, 256, est, d, ctx->sel, cnt_gt, cnt_eq, nt);
+    SAMS_LAUNCH(ctx, KID_SEL_COUNT, k_sel_count, tgrid, 256, keys, len, ctx->sel, cnt_gt, cnt_eq, nt);
     SAMS_LAUNCH(ctx, KID_SEL_SCAN, k_sel_scan, 1, 1024, cnt_gt, cnt_eq, nt, ctx->sel, sel_base, eq_base);
-    SAMS_LAUNCH(ctx, KID_SEL_WRITE, k_sel_write, tgrid, 256, est, d, ctx->sel, sel_base, eq_base, nt,
-                ctx->k, idx, est_sel);
+    SAMS_LAUNCH(ctx, KID_SEL_WRITE, k_sel_write, tgrid, 256, keys, len, ctx->sel, sel_base, eq_base, nt, k, idx,
+                val_sel);
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+int enqueue_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_in, int64_t k_out,
+                   int32_t *idx_out, float *delta_out)
+{
+    int32_t *pos = reinterpret_cast<int32_t *>(ctx->est);             // the estimate scratch is free at this point
+    SAMS_TRY(enqueue_select(ctx, delta_in, k_in, k_out, pos, delta_out));
+    SAMS_LAUNCH(ctx, KID_REFINE_MAP, k_refine_map, grid_for(k_out, 256), 256, idx_in, pos, k_out, idx_out);
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
 }

@@ -22,7 +22,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 # every symbol include/sams.h declares
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_last_hip_error", "sams_hash_dump",
            "sams_configure", "sams_sketch_mode", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
-           "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk",
+           "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk", "topk_refine",
            "amsgrad_ef_update"]
 
 _lib = None
@@ -64,6 +64,7 @@ def load() -> ctypes.CDLL:
     lib.unsketch_topk.argtypes = [vp, vp, vp, vp, vp]
     lib.unsketch_estimates.argtypes = [vp, vp, vp, vp]
     lib.gather_topk.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.topk_refine.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.amsgrad_ef_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
     for name in EXPORTS:
         if name not in ("sams_scratch_bytes", "sams_profile_name"):
@@ -180,6 +181,12 @@ class Context:
             self._h, _ptr(u, torch.float32, (self.n, self.d), "u"), _ptr(vhat, torch.float32, (self.d,), "vhat"),
             _ptr(idx, torch.int32, (self.k,), "idx"), _ptr(U_workers, torch.float32, (self.n, self.k), "U_workers"),
             _ptr(delta, torch.float32, (self.k,), "delta")), "gather_topk")
+
+    def topk_refine(self, idx_in, delta_in, k_out, idx_out, delta_out):
+        _check(self._lib.topk_refine(
+            self._h, _ptr(idx_in, torch.int32, (self.k,), "idx_in"), _ptr(delta_in, torch.float32, (self.k,), "delta_in"),
+            int(k_out), _ptr(idx_out, torch.int32, (k_out,), "idx_out"),
+            _ptr(delta_out, torch.float32, (k_out,), "delta_out")), "topk_refine")
 
     def amsgrad_ef_update(self, g_next, m, e_u, v, vhat, x, idx, delta, k_sel, beta1, beta2, lr, ef_ratio=1.0):
         nd = (self.n, self.d)

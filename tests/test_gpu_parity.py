@@ -254,6 +254,63 @@ def test_amsgrad_ef_update_head_and_tail_bit_exact(sams, path, d, n, r, c, k):
             assert np.array_equal(host(got), want)
 
 
+@pytest.mark.parametrize("k_in,k_out", [(1, 1), (64, 64), (1000, 37), (50_000, 12_500), (400_000, 50_000)])
+def test_topk_refine_bit_exact_with_ties(sams, k_in, k_out):
+    d = 3_000_000
+    rng = np.random.default_rng(k_in)
+    cand = np.sort(rng.choice(d, k_in, replace=False)).astype(np.int32)
+    vals = (rng.integers(-9, 10, k_in) / 4.0).astype(np.float32)
+    vals[rng.integers(0, k_in, max(1, k_in // 8))] = -0.0
+    idx, delta = Oracle("f32").refine(cand, vals, k_out)
+    with sams.Context(d, 2, 3, 1000, k_in, inputs.hash_params(3)) as ctx:
+        io = torch.full((k_out,), -1, device="cuda", dtype=torch.int32)
+        do = torch.empty(k_out, device="cuda")
+        ctx.topk_refine(dev(cand), dev(vals), k_out, io, do)
+        assert np.array_equal(host(io), idx) and np.array_equal(host(do), delta)
+
+
+@pytest.mark.parametrize("wl,d,P", [("C4", 400_000, 4), ("P1", 600_000, 8), ("P2a", 60_000, 4)])
+def test_chained_steps_with_overselection_follow_the_oracle(sams, wl, d, P):
+    """The paper's second round (Sec. III-A) with P*k candidates: context created with k = P*k, top-k refined
+    from the exact values; every step is re-derived by the oracle from the GPU's previous state."""
+    w = inputs.WORKLOADS[wl].scaled(d) if d != inputs.WORKLOADS[wl].d else inputs.WORKLOADS[wl]
+    k, kc = w.k, P * w.k
+    gs = inputs.GradientStream(w, device="cuda")
+    hp = inputs.hash_params(w.r, seed=w.seed)
+    o = Oracle("f32")
+    steps = 4
+    with sams.Context(w.d, w.n, w.r, w.c, kc, hp) as ctx:
+        b = sams.Buffers(w.d, w.n, w.r, w.c, kc, w.eps, gs.x1())
+        idx_f = torch.empty(k, device="cuda", dtype=torch.int32)
+        delta_f = torch.empty(k, device="cuda")
+        G = [gs.step(t) for t in range(steps)]
+        st = dict(m=np.zeros((w.n, w.d), np.float32), e=np.zeros((w.n, w.d), np.float32),
+                  v=np.full(w.d, w.eps, np.float32), vhat=np.full(w.d, w.eps, np.float32), x=host(b.x).copy())
+        mask = None
+        ctx.amsgrad_ef_update(G[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+        for t in range(steps):
+            o.head(host(G[t]), st["m"], st["e"], st["v"], st["vhat"], mask, w.beta1, w.beta2)
+            assert np.array_equal(host(b.e_u), st["e"]) and np.array_equal(host(b.vhat), st["vhat"]), t
+            ctx.sketch_accumulate(b.e_u, b.S_workers)
+            ctx.sketch_reduce(b.S_workers, b.S_mean)
+            ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
+            ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+            ctx.topk_refine(b.idx, b.delta, k, idx_f, delta_f)
+            est = o.unsketch(host(b.S_mean), st["vhat"], w.d, hp)
+            cand = o.topk(est, kc)
+            assert np.array_equal(host(b.idx), cand), t
+            _, dcand = o.gather(st["e"], st["vhat"], cand)
+            assert np.array_equal(host(b.delta), dcand), t
+            idx, delta = o.refine(cand, dcand, k)
+            assert np.array_equal(host(idx_f), idx) and np.array_equal(host(delta_f), delta), t
+            g_next = G[t + 1] if t + 1 < steps else None
+            ctx.amsgrad_ef_update(g_next, b.m, b.e_u, b.v, b.vhat, b.x, idx_f, delta_f, k, w.beta1, w.beta2, w.lr)
+            o.tail(st["e"], st["x"], idx, delta, w.lr)
+            mask = np.zeros(w.d, np.uint8)
+            mask[idx] = 1
+            assert np.array_equal(host(b.x), st["x"]), t
+
+
 def gpu_state(b):
     return dict(m=host(b.m).copy(), e=host(b.e_u).copy(), v=host(b.v).copy(), vhat=host(b.vhat).copy(),
                 x=host(b.x).copy())

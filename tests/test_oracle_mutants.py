@@ -31,6 +31,7 @@ MUTANTS = {  # name: (file, text to find, replacement)
     "top-k by signed value": ("sams_oracle_impl.h", "p[l].mag = est[l] < (REAL)0 ? -est[l] : est[l];", "p[l].mag = est[l];"),
     "ties to the larger index": ("sams_oracle_impl.h", "return (a->idx > b->idx) - (a->idx < b->idx);",
                                  "return (a->idx < b->idx) - (a->idx > b->idx);"),
+    "refine keeps the coordinates but the wrong values": ("sams_oracle_impl.h", "delta_out[q] = delta_in[pos[q]];", "delta_out[q] = delta_in[q];"),
     "gather sums instead of averaging": ("sams_oracle_impl.h", "REAL mean = acc / (REAL)n;", "REAL mean = acc;"),
     "gather skips the vhat scaling": ("sams_oracle_impl.h", "delta[q] = vhat ? mean / FN(orc_sqrt)(vhat[l]) : mean;",
                                       "delta[q] = mean;"),
@@ -60,6 +61,7 @@ PINS = [  # cheap first; a mutant is caught as soon as one of them fails
     pins.test_exact_recovery_equals_dense_topk_error_feedback_amsgrad,
     pins.test_lemma3_auxiliary_sequence_and_structural_invariants,
     pins.test_lemma3_holds_with_a_decaying_step_size,
+    lambda: pins.test_refine_matches_full_sort_with_ties("f64"),
     pins.test_sketch_then_unsketch_meets_count_sketch_error_bound,
 ]
 

@@ -370,6 +370,78 @@ def test_lemma3_holds_with_a_decaying_step_size():
         alpha_prev = alpha
 
 
+def step_with_overselection(o, g, st, hp, c, k, P, b1, b2, lr):
+    """One iteration of Alg. 2 with the second round of Sec. III-A: P*k candidates from the sketch, their exact
+    values from the workers, then the top-k among those."""
+    n, d = g.shape
+    o.head(g, st["m"], st["e"], st["v"], st["vhat"], st["in_prev"], b1, b2)
+    u = st["e"].copy()
+    S = o.sketch_mean(np.stack([o.sketch(st["e"][i], hp, c) for i in range(n)]))
+    est = o.unsketch(S, st["vhat"], d, hp)
+    cand = o.topk(est, P * k)
+    _, dcand = o.gather(st["e"], st["vhat"], cand)
+    idx, delta = o.refine(cand, dcand, k)
+    o.tail(st["e"], st["x"], idx, delta, lr)
+    st["in_prev"][...] = 0
+    st["in_prev"][idx] = 1
+    return dict(u=u, est=est, cand=cand, dcand=dcand, idx=idx, delta=delta)
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_refine_matches_full_sort_with_ties(prec):
+    o = Oracle(prec)
+    rng = np.random.default_rng(3)
+    for k_in, k_out in [(1, 1), (40, 40), (40, 7), (5000, 1200), (5000, 4999)]:
+        cand = np.sort(rng.choice(100_000, k_in, replace=False)).astype(np.int32)
+        vals = (rng.integers(-5, 6, k_in) / 2.0).astype(o.dtype)                 # many ties, zeros of both signs
+        vals[rng.integers(0, k_in, max(1, k_in // 8))] = -0.0
+        order = np.lexsort((cand, -np.abs(vals)))[:k_out]
+        keep = np.sort(order)
+        idx, delta = o.refine(cand, vals, k_out)
+        assert np.array_equal(idx, cand[keep]) and np.array_equal(delta, vals[keep])
+
+
+def test_overselection_changes_nothing_under_exact_recovery():
+    # c >= d with identity bucket hashes: the estimates are the exact values, so the k largest of the P*k
+    # candidates are the k largest overall and the run must equal the sketch-free dense algorithm.
+    o = Oracle("f64")
+    d, n, k, P, T, r = 400, 3, 25, 4, 8, 5
+    b1, b2, lr, eps = 0.9, 0.99, 1e-2, 1e-6
+    rng = np.random.default_rng(21)
+    G = [rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 0, d) for _ in range(T)]
+    x1 = rng.standard_normal(d)
+    hp = inputs.identity_hash_params(r, seed=4)
+    st = o.init_state(x1, n, eps)
+    ref = dense_topk_ef_amsgrad(G, x1, k, b1, b2, lr, eps)
+    for t in range(T):
+        out = step_with_overselection(o, np.ascontiguousarray(G[t]), st, hp, d + 3, k, P, b1, b2, lr)
+        assert np.array_equal(out["idx"], np.flatnonzero(ref[t]["sel"]))
+        np.testing.assert_allclose(st["x"], ref[t]["x"], rtol=1e-11, atol=1e-14)
+        assert set(out["idx"].tolist()) <= set(out["cand"].tolist())
+
+
+def test_lemma3_holds_with_overselection_and_collisions():
+    o = Oracle("f64")
+    d, n, k, P, T, r, c = 3000, 4, 30, 4, 10, 5, 160
+    b1, b2, lr, eps = 0.9, 0.99, 1e-3, 1e-8
+    w = inputs.WORKLOADS["C4"].scaled(d, c=c, k=k, n=n)
+    gs = inputs.GradientStream(w)
+    hp = inputs.hash_params(r, seed=5)
+    x1 = gs.x1().numpy().astype(np.float64)
+    st = o.init_state(x1, n, eps)
+    xt = x1.copy()
+    for t in range(T):
+        g = gs.step(t).numpy().astype(np.float64)
+        out = step_with_overselection(o, g, st, hp, c, k, P, b1, b2, lr)
+        xt = xt - lr * st["m"].mean(axis=0) / np.sqrt(st["vhat"])
+        carried = lr * st["e"].mean(axis=0) / np.sqrt(st["vhat"])
+        assert np.abs(st["x"] - xt - carried).max() <= 1e-12 * (np.abs(st["x"]).max() + np.abs(carried).max())
+        assert len(out["idx"]) == k and not st["e"][:, out["idx"]].any()
+        # the exact values decide: every kept candidate is at least as large as every dropped one
+        kept = np.isin(out["cand"], out["idx"])
+        assert np.abs(out["dcand"][kept]).min() >= np.abs(out["dcand"][~kept]).max()
+
+
 def test_plain_unsketch_variant_skips_the_vhat_scaling():
     # Alg. 1 uses the original operator U_0 (no second input): est and Delta carry no 1/sqrt(vhat)
     o = Oracle("f64")
