@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--cpu-sample-d", type=int, default=2_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept resident")
+    ap.add_argument("--overselect", type=int, default=1,
+                    help="P of the paper's second round: P*k candidates, then topk_refine (default 1: none)")
     ap.add_argument("--tune", default="fuse_head=1",
                     help="library tunables (sams_configure), e.g. fuse_head=1,tile_log2=14,win_log2=15")
     args = ap.parse_args()
@@ -109,11 +111,15 @@ def main():
         sams.sams_configure(key, int(val))
     w = inputs.WORKLOADS[args.workload]
     d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
+    P = max(1, args.overselect)
+    kc = P * k                                   # candidates taken from the sketch
     torch.cuda.set_device(0)
     gs = inputs.GradientStream(w, device="cuda")
     hp = inputs.hash_params(r, seed=w.seed)
-    ctx = sams.Context(d, n, r, c, k, hp)
-    b = sams.Buffers(d, n, r, c, k, w.eps, gs.x1())
+    ctx = sams.Context(d, n, r, c, kc, hp)
+    b = sams.Buffers(d, n, r, c, kc, w.eps, gs.x1())
+    idx_f = torch.empty(k, device="cuda", dtype=torch.int32) if P > 1 else b.idx
+    delta_f = torch.empty(k, device="cuda") if P > 1 else b.delta
     pool = [gs.step(t) for t in range(max(1, args.pool))]
     torch.cuda.synchronize()
 
@@ -122,7 +128,9 @@ def main():
         ctx.sketch_reduce(b.S_workers, b.S_mean)
         ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
         ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
-        ctx.amsgrad_ef_update(pool[(t + 1) % len(pool)], b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, k,
+        if P > 1:
+            ctx.topk_refine(b.idx, b.delta, k, idx_f, delta_f)
+        ctx.amsgrad_ef_update(pool[(t + 1) % len(pool)], b.m, b.e_u, b.v, b.vhat, b.x, idx_f, delta_f, k,
                               w.beta1, w.beta2, w.lr, 1.0)
 
     # head of the first iteration, then warm-up
@@ -173,7 +181,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: d={d}, n={n} simulated workers, sketch {r}x{c}, k={k}, "
                                f"{w.noise} gradients in {w.nseg} segments + {w.heavy} heavy coordinates",
-                   "d": d, "n": n, "r": r, "c": c, "k": k, "tunables": args.tune},
+                   "d": d, "n": n, "r": r, "c": c, "k": k, "tunables": args.tune, "overselect_P": P},
         "worker_coords_per_s": n * d / (ms_per_step * 1e-3),
         "device_ms_per_step": ev_ms_per_step,
         "step_algorithmic_bytes": step_bytes,
