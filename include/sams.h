@@ -212,6 +212,20 @@ int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, 
                       float *x, const int32_t *idx, const float *delta, int64_t k_sel, float beta1,
                       float beta2, float lr, float ef_ratio);
 
+/*
+ * Stage 5 of the parameter-averaging variant (Alg. 1): same tail as amsgrad_ef_update, and the head
+ *       m[i][l]    = beta1 * m[i][l] + (1-beta1) * g_next[i][l]
+ *       v_workers[i][l]    = beta2 * v_workers[i][l] + (1-beta2) * g_next[i][l]^2
+ *       vhat_workers[i][l] = max(vhat_workers[i][l], v_workers[i][l])
+ *       e_u[i][l]  = m[i][l] / sqrt(vhat_workers[i][l]) + ef_ratio * e_u[i][l]
+ * with every worker keeping its own second moments.  The other stages are called with vhat = NULL (Alg. 1 uses
+ * the plain unsketch operator and the values it averages are already scaled).
+ *   v_workers, vhat_workers [n][d] in place (initially eps);  everything else as in amsgrad_ef_update.
+ */
+int amsgrad_ef_update_pa(sams_ctx *ctx, const float *g_next, float *m, float *e_u, float *v_workers,
+                         float *vhat_workers, float *x, const int32_t *idx, const float *delta, int64_t k_sel,
+                         float beta1, float beta2, float lr, float ef_ratio);
+
 #ifdef __cplusplus
 }
 #endif

@@ -175,6 +175,15 @@ class Oracle:
                              ctypes.c_int64(d), R(self.dtype(beta1)), R(self.one_minus(beta1)),
                              R(self.dtype(beta2)), R(self.one_minus(beta2)), R(self.dtype(rho)))
 
+    def head_pa(self, g, m, e_u, v_w, vhat_w, beta1, beta2, rho=1.0):
+        """Alg. 1 worker lines, in place on m, e_u (receives u), v_w, vhat_w (all [n][d])."""
+        self._chk(g, m, e_u, v_w, vhat_w)
+        n, d = g.shape
+        R = self.creal
+        self._fn("orc_head_pa")(_p(g), _p(m), _p(e_u), _p(v_w), _p(vhat_w), ctypes.c_int32(n), ctypes.c_int64(d),
+                                R(self.dtype(beta1)), R(self.one_minus(beta1)), R(self.dtype(beta2)),
+                                R(self.one_minus(beta2)), R(self.dtype(rho)))
+
     def tail(self, e_u, x, idx, delta, lr):
         """In place on e_u (u in, e out) and x."""
         self._chk(e_u, x, delta)

@@ -192,6 +192,24 @@ void FN(orc_head)(const REAL *g /* [n][d] */, REAL *m /* [n][d] */, REAL *e_u /*
     }
 }
 
+/* Alg. 1 (parameter averaging), worker lines of iteration t; every worker keeps its own second moments:
+ *   m_t = beta1 m_{t-1} + (1-beta1) g_t ;  v_t = beta2 v_{t-1} + (1-beta2) g_t^2 ;  vhat_t = max(vhat_{t-1}, v_t)
+ *   u = m_t / sqrt(vhat_t) + rho e_{t-1}        (the vector that is sketched; written over e)
+ * The rest of the iteration is Alg. 1's master lines: plain unsketch U_0 (no second input), Top-k, and the
+ * same e_t / x_{t+1} lines as in Alg. 2 (orc_tail). */
+void FN(orc_head_pa)(const REAL *g /* [n][d] */, REAL *m, REAL *e_u, REAL *v_w, REAL *vhat_w /* [n][d] each */,
+                     int32_t n, int64_t d, REAL beta1, REAL omb1, REAL beta2, REAL omb2, REAL rho)
+{
+    for (int64_t t = 0; t < (int64_t)n * d; ++t) {
+        REAL mm = beta1 * m[t] + omb1 * g[t];
+        REAL vv = beta2 * v_w[t] + omb2 * (g[t] * g[t]);
+        m[t] = mm;
+        v_w[t] = vv;
+        if (vv > vhat_w[t]) vhat_w[t] = vv;
+        e_u[t] = mm / FN(orc_sqrt)(vhat_w[t]) + rho * e_u[t];
+    }
+}
+
 /* Alg. 2, second half of iteration t.
  *   e_t^(i) = u^(i) off I_t, 0 on I_t (proof of Lemma 3);  x_{t+1} = x_t - alpha_t Delta_t,
  *   Delta_t being non-zero only on I_t. */

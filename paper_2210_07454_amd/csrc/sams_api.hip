@@ -15,7 +15,7 @@ static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
     "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds", "k_bin_lookup",
-    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map"};
+    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map", "k_head_pa"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -298,6 +298,21 @@ int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, 
         else
             SAMS_TRY(enqueue_head(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
     }
+    return SAMS_OK;
+}
+
+int amsgrad_ef_update_pa(sams_ctx *ctx, const float *g_next, float *m, float *e_u, float *v_workers,
+                         float *vhat_workers, float *x, const int32_t *idx, const float *delta, int64_t k_sel,
+                         float beta1, float beta2, float lr, float ef_ratio)
+{
+    if (!ctx || !m || !e_u || !v_workers || !vhat_workers || !x) return SAMS_EINVAL;
+    if (k_sel < 0 || k_sel > ctx->k || (k_sel > 0 && (!idx || !delta))) return SAMS_EINVAL;
+    if (!aligned16(g_next) || !aligned16(m) || !aligned16(e_u) || !aligned16(v_workers) ||
+        !aligned16(vhat_workers) || !aligned16(x) || !aligned16(idx) || !aligned16(delta))
+        return SAMS_EINVAL;
+    ctx->plan.staged_u = nullptr;                                    // e_u is about to change
+    SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
+    if (g_next) SAMS_TRY(enqueue_head_pa(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio));
     return SAMS_OK;
 }
 

@@ -44,7 +44,7 @@ enum KernelId {
     KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
     KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
     KID_GATHER, KID_PLAN_BUILD, KID_BIN_SCATTER, KID_BIN_ACCUMULATE, KID_SKETCH_LDS, KID_BIN_LOOKUP,
-    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_COUNT
+    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_HEAD_PA, KID_COUNT
 };
 const char *kernel_name(int kid);
 
@@ -177,6 +177,8 @@ int enqueue_tail(sams_ctx *ctx, float *e_u, float *x, const int32_t *idx, const 
                  int64_t k_sel, float lr, bool zero_e);
 int enqueue_head(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
                  float beta1, float beta2, float rho);
+int enqueue_head_pa(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v_w, float *vhat_w, float beta1,
+                    float beta2, float rho);
 int enqueue_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean);
 int enqueue_gather(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx,
                    float *U_workers, float *delta);

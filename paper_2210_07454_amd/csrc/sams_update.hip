@@ -124,6 +124,69 @@ k_gather(const float *__restrict__ u, const float *__restrict__ vhat, const int3
     delta[q] = vhat ? (mean / sqrtf(vhat[l])) : mean;
 }
 
+// Head of Alg. 1 (parameter averaging): per-worker second moments, u = m / sqrt(vhat) + rho * e.
+// Purely elementwise over the n*d entries; e is taken as zero on the recorded index set (bitmap over d).
+template <int VEC>
+__global__ void __launch_bounds__(256)
+k_head_pa(const float *__restrict__ g, float *__restrict__ m, float *__restrict__ e, float *__restrict__ vw,
+          float *__restrict__ vhw, const uint32_t *__restrict__ bitmap, int64_t d, float beta1, float omb1,
+          float beta2, float omb2, float rho)
+{
+    const int64_t l0 = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) * VEC;
+    if (l0 >= d) return;
+    const int64_t off = (int64_t)blockIdx.y * d + l0;
+    const uint32_t selbits = (bitmap[l0 >> 5] >> (l0 & 31)) & (VEC == 4 ? 0xFu : 1u);
+    float gv[VEC], mv[VEC], ev[VEC], vv[VEC], vh[VEC];
+    if (VEC == 4) {
+        const float4 a = *reinterpret_cast<const float4 *>(g + off), b = *reinterpret_cast<const float4 *>(m + off),
+                     cc = *reinterpret_cast<const float4 *>(e + off), p = *reinterpret_cast<const float4 *>(vw + off),
+                     q = *reinterpret_cast<const float4 *>(vhw + off);
+        gv[0] = a.x; gv[1] = a.y; gv[2] = a.z; gv[3] = a.w;
+        mv[0] = b.x; mv[1] = b.y; mv[2] = b.z; mv[3] = b.w;
+        ev[0] = cc.x; ev[1] = cc.y; ev[2] = cc.z; ev[3] = cc.w;
+        vv[0] = p.x; vv[1] = p.y; vv[2] = p.z; vv[3] = p.w;
+        vh[0] = q.x; vh[1] = q.y; vh[2] = q.z; vh[3] = q.w;
+    } else {
+        gv[0] = g[off]; mv[0] = m[off]; ev[0] = e[off]; vv[0] = vw[off]; vh[0] = vhw[off];
+    }
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) {
+        const float mm = (beta1 * mv[t]) + (omb1 * gv[t]);
+        const float v2 = (beta2 * vv[t]) + (omb2 * (gv[t] * gv[t]));
+        const float ein = ((selbits >> t) & 1u) ? 0.0f : ev[t];
+        mv[t] = mm;
+        vv[t] = v2;
+        if (v2 > vh[t]) vh[t] = v2;
+        ev[t] = (mm / sqrtf(vh[t])) + (rho * ein);
+    }
+    if (VEC == 4) {
+        *reinterpret_cast<float4 *>(m + off) = make_float4(mv[0], mv[1], mv[2], mv[3]);
+        *reinterpret_cast<float4 *>(e + off) = make_float4(ev[0], ev[1], ev[2], ev[3]);
+        *reinterpret_cast<float4 *>(vw + off) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        *reinterpret_cast<float4 *>(vhw + off) = make_float4(vh[0], vh[1], vh[2], vh[3]);
+    } else {
+        m[off] = mv[0]; e[off] = ev[0]; vw[off] = vv[0]; vhw[off] = vh[0];
+    }
+}
+
+int enqueue_head_pa(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v_w, float *vhat_w, float beta1,
+                    float beta2, float rho)
+{
+    const int64_t d = ctx->d;
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    if ((d & 3) == 0) {
+        ProfScope ps(ctx, KID_HEAD_PA);
+        hipLaunchKernelGGL(k_head_pa<4>, dim3((unsigned)grid_for(d / 4, 256), (unsigned)ctx->n), dim3(256), 0,
+                           ctx->stream, g, m, e_u, v_w, vhat_w, ctx->bitmap, d, beta1, omb1, beta2, omb2, rho);
+    } else {
+        ProfScope ps(ctx, KID_HEAD_PA);
+        hipLaunchKernelGGL(k_head_pa<1>, dim3((unsigned)grid_for(d, 256), (unsigned)ctx->n), dim3(256), 0,
+                           ctx->stream, g, m, e_u, v_w, vhat_w, ctx->bitmap, d, beta1, omb1, beta2, omb2, rho);
+    }
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
 int enqueue_tail(sams_ctx *ctx, float *e_u, float *x, const int32_t *idx, const float *delta,
                  int64_t k_sel, float lr, bool zero_e)
 {

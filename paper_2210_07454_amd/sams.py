@@ -23,7 +23,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_last_hip_error", "sams_hash_dump",
            "sams_configure", "sams_sketch_mode", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk", "topk_refine",
-           "amsgrad_ef_update"]
+           "amsgrad_ef_update", "amsgrad_ef_update_pa"]
 
 _lib = None
 
@@ -66,6 +66,7 @@ def load() -> ctypes.CDLL:
     lib.gather_topk.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.topk_refine.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.amsgrad_ef_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
+    lib.amsgrad_ef_update_pa.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
     for name in EXPORTS:
         if name not in ("sams_scratch_bytes", "sams_profile_name"):
             getattr(lib, name).restype = ctypes.c_int
@@ -199,6 +200,22 @@ class Context:
             _ptr(vhat, torch.float32, (self.d,), "vhat"), _ptr(x, torch.float32, (self.d,), "x"),
             _ptr(idx, torch.int32, None, "idx"), _ptr(delta, torch.float32, None, "delta"), int(k_sel),
             float(beta1), float(beta2), float(lr), float(ef_ratio)), "amsgrad_ef_update")
+
+
+    def _update_pa(self, g_next, m, e_u, v_w, vhat_w, x, idx, delta, k_sel, beta1, beta2, lr, ef_ratio):
+        nd = (self.n, self.d)
+        _check(self._lib.amsgrad_ef_update_pa(
+            self._h, _ptr(g_next, torch.float32, nd, "g_next"), _ptr(m, torch.float32, nd, "m"),
+            _ptr(e_u, torch.float32, nd, "e_u"), _ptr(v_w, torch.float32, nd, "v_workers"),
+            _ptr(vhat_w, torch.float32, nd, "vhat_workers"), _ptr(x, torch.float32, (self.d,), "x"),
+            _ptr(idx, torch.int32, None, "idx"), _ptr(delta, torch.float32, None, "delta"), int(k_sel),
+            float(beta1), float(beta2), float(lr), float(ef_ratio)), "amsgrad_ef_update_pa")
+
+    def amsgrad_ef_update_pa(self, g_next, m, e_u, v_workers, vhat_workers, x, idx, delta, k_sel, beta1, beta2, lr,
+                             ef_ratio=1.0):
+        if k_sel and (idx is None or delta is None or idx.numel() < k_sel or delta.numel() < k_sel):
+            raise ValueError("idx/delta shorter than k_sel")
+        self._update_pa(g_next, m, e_u, v_workers, vhat_workers, x, idx, delta, k_sel, beta1, beta2, lr, ef_ratio)
 
 
 class Buffers:

@@ -311,6 +311,68 @@ def test_chained_steps_with_overselection_follow_the_oracle(sams, wl, d, P):
             assert np.array_equal(host(b.x), st["x"]), t
 
 
+@pytest.mark.parametrize("d,n,r,c,k", SHAPES)
+def test_amsgrad_ef_update_pa_bit_exact(sams, d, n, r, c, k):
+    rng = np.random.default_rng(d + 7)
+    o = Oracle("f32")
+    b1, b2, lr = 0.9, 0.999, 1e-3
+    f = lambda *s: (rng.standard_normal(s) * 10.0 ** rng.uniform(-4, 0, s)).astype(np.float32)
+    g1, g2, m, e, x = f(n, d), f(n, d), f(n, d), f(n, d), f(d)
+    vw = (10.0 ** rng.uniform(-8, -2, (n, d))).astype(np.float32)
+    vhw = np.maximum(vw, (10.0 ** rng.uniform(-8, -2, (n, d))).astype(np.float32))
+    idx = np.sort(rng.choice(d, k, replace=False)).astype(np.int32)
+    delta = f(k)
+    with sams.Context(d, n, r, c, k, inputs.hash_params(r)) as ctx:
+        md, ed, vd, vhd, xd = dev(m), dev(e), dev(vw), dev(vhw), dev(x)
+        ctx.amsgrad_ef_update_pa(dev(g1), md, ed, vd, vhd, xd, None, None, 0, b1, b2, lr)
+        o.head_pa(g1, m, e, vw, vhw, b1, b2)
+        for got, want in ((md, m), (ed, e), (vd, vw), (vhd, vhw), (xd, x)):
+            assert np.array_equal(host(got), want)
+        ctx.amsgrad_ef_update_pa(dev(g2), md, ed, vd, vhd, xd, dev(idx), dev(delta), k, b1, b2, lr, 1.25)
+        o.tail(e, x, idx, delta, lr)
+        o.head_pa(g2, m, e, vw, vhw, b1, b2, rho=1.25)
+        for got, want in ((md, m), (ed, e), (vd, vw), (vhd, vhw), (xd, x)):
+            assert np.array_equal(host(got), want)
+        ctx.amsgrad_ef_update_pa(None, md, ed, vd, vhd, xd, dev(idx), dev(delta), k, b1, b2, lr)
+        o.tail(e, x, idx, delta, lr)
+        assert np.array_equal(host(ed), e) and np.array_equal(host(xd), x)
+
+
+@pytest.mark.parametrize("wl,d", [("C2", 300_000), ("P1", 400_000), ("P2b", 60_000)])
+def test_chained_parameter_averaging_steps_follow_the_oracle(sams, wl, d):
+    """Alg. 1 end to end: per-worker second moments, plain unsketch operator, unscaled second round."""
+    w = inputs.WORKLOADS[wl].scaled(d) if d != inputs.WORKLOADS[wl].d else inputs.WORKLOADS[wl]
+    gs = inputs.GradientStream(w, device="cuda")
+    hp = inputs.hash_params(w.r, seed=w.seed)
+    o = Oracle("f32")
+    steps = 4
+    with sams.Context(w.d, w.n, w.r, w.c, w.k, hp) as ctx:
+        b = sams.Buffers(w.d, w.n, w.r, w.c, w.k, w.eps, gs.x1())
+        vw = torch.full((w.n, w.d), w.eps, device="cuda")
+        vhw = torch.full((w.n, w.d), w.eps, device="cuda")
+        st = dict(m=np.zeros((w.n, w.d), np.float32), e=np.zeros((w.n, w.d), np.float32),
+                  vw=np.full((w.n, w.d), w.eps, np.float32), vhw=np.full((w.n, w.d), w.eps, np.float32),
+                  x=host(b.x).copy())
+        G = [gs.step(t) for t in range(steps)]
+        ctx.amsgrad_ef_update_pa(G[0], b.m, b.e_u, vw, vhw, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+        for t in range(steps):
+            o.head_pa(host(G[t]), st["m"], st["e"], st["vw"], st["vhw"], w.beta1, w.beta2)
+            assert np.array_equal(host(b.e_u), st["e"]) and np.array_equal(host(vhw), st["vhw"]), t
+            ctx.sketch_accumulate(b.e_u, b.S_workers)
+            ctx.sketch_reduce(b.S_workers, b.S_mean)
+            ctx.unsketch_topk(b.S_mean, None, b.idx, None)
+            ctx.gather_topk(b.e_u, None, b.idx, b.U_workers, b.delta)
+            est = o.unsketch(host(b.S_mean), None, w.d, hp)
+            idx = o.topk(est, w.k)
+            assert np.array_equal(host(b.idx), idx), t
+            _, delta = o.gather(st["e"], None, idx)
+            assert np.array_equal(host(b.delta), delta), t
+            g_next = G[t + 1] if t + 1 < steps else None
+            ctx.amsgrad_ef_update_pa(g_next, b.m, b.e_u, vw, vhw, b.x, b.idx, b.delta, w.k, w.beta1, w.beta2, w.lr)
+            o.tail(st["e"], st["x"], idx, delta, w.lr)
+            assert np.array_equal(host(b.x), st["x"]), t
+
+
 def gpu_state(b):
     return dict(m=host(b.m).copy(), e=host(b.e_u).copy(), v=host(b.v).copy(), vhat=host(b.vhat).copy(),
                 x=host(b.x).copy())

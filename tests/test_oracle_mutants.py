@@ -32,6 +32,11 @@ MUTANTS = {  # name: (file, text to find, replacement)
     "ties to the larger index": ("sams_oracle_impl.h", "return (a->idx > b->idx) - (a->idx < b->idx);",
                                  "return (a->idx < b->idx) - (a->idx > b->idx);"),
     "refine keeps the coordinates but the wrong values": ("sams_oracle_impl.h", "delta_out[q] = delta_in[pos[q]];", "delta_out[q] = delta_in[q];"),
+    "PA: second moment fed with g, not g^2": ("sams_oracle_impl.h", "omb2 * (g[t] * g[t])", "omb2 * g[t]"),
+    "PA: scaling by v instead of vhat": ("sams_oracle_impl.h", "e_u[t] = mm / FN(orc_sqrt)(vhat_w[t]) + rho * e_u[t];",
+                                         "e_u[t] = mm / FN(orc_sqrt)(vv) + rho * e_u[t];"),
+    "PA: error feedback also scaled": ("sams_oracle_impl.h", "e_u[t] = mm / FN(orc_sqrt)(vhat_w[t]) + rho * e_u[t];",
+                                       "e_u[t] = (mm + rho * e_u[t]) / FN(orc_sqrt)(vhat_w[t]);"),
     "gather sums instead of averaging": ("sams_oracle_impl.h", "REAL mean = acc / (REAL)n;", "REAL mean = acc;"),
     "gather skips the vhat scaling": ("sams_oracle_impl.h", "delta[q] = vhat ? mean / FN(orc_sqrt)(vhat[l]) : mean;",
                                       "delta[q] = mean;"),
@@ -62,6 +67,9 @@ PINS = [  # cheap first; a mutant is caught as soon as one of them fails
     pins.test_lemma3_auxiliary_sequence_and_structural_invariants,
     pins.test_lemma3_holds_with_a_decaying_step_size,
     lambda: pins.test_refine_matches_full_sort_with_ties("f64"),
+    pins.test_pa_single_coordinate_closed_form,
+    pins.test_pa_without_compression_averages_per_worker_amsgrad_steps,
+    pins.test_pa_auxiliary_sequence_identity_with_decaying_step_size,
     pins.test_sketch_then_unsketch_meets_count_sketch_error_bound,
 ]
 

@@ -442,6 +442,102 @@ def test_lemma3_holds_with_overselection_and_collisions():
         assert np.abs(out["dcand"][kept]).min() >= np.abs(out["dcand"][~kept]).max()
 
 
+# --------------------------------------------------------- Alg. 1 (parameter averaging)
+def step_pa(o, g, st, hp, c, k, b1, b2, lr, rho=1.0):
+    """One iteration of Alg. 1 from the oracle's stage routines (plain unsketch, unscaled gather)."""
+    n, d = g.shape
+    o.head_pa(g, st["m"], st["e"], st["vw"], st["vhw"], b1, b2, rho)
+    u = st["e"].copy()
+    S = o.sketch_mean(np.stack([o.sketch(st["e"][i], hp, c) for i in range(n)]))
+    est = o.unsketch(S, None, d, hp)
+    idx = o.topk(est, k)
+    _, delta = o.gather(st["e"], None, idx)
+    o.tail(st["e"], st["x"], idx, delta, lr)
+    return dict(u=u, est=est, idx=idx, delta=delta)
+
+
+def init_pa(o, x1, n, eps):
+    d = x1.shape[0]
+    return dict(m=np.zeros((n, d), o.dtype), e=np.zeros((n, d), o.dtype), vw=np.full((n, d), eps, o.dtype),
+                vhw=np.full((n, d), eps, o.dtype), x=np.array(x1, dtype=o.dtype))
+
+
+def test_pa_single_coordinate_closed_form():
+    # d = k = n = 1, constant gradient g:  m_t = (1-b1^t) g ;  v_t = b2^t eps + (1-b2^t) g^2 (fed from t = 1 on:
+    # Alg. 1 has no index-set restriction) ;  x_{t+1} = x_t - lr m_t / sqrt(vhat_t) ;  e = 0
+    o = Oracle("f64")
+    b1, b2, lr, eps, g, T = 0.9, 0.99, 1e-3, 1e-8, -0.21, 20
+    st = init_pa(o, np.array([0.3]), 1, eps)
+    hp = inputs.hash_params(2, seed=1)
+    x, vh = 0.3, eps
+    for t in range(1, T + 1):
+        step_pa(o, np.full((1, 1), g), st, hp, 4, 1, b1, b2, lr)
+        m = (1 - b1 ** t) * g
+        v = b2 ** t * eps + (1 - b2 ** t) * g * g
+        vh = max(vh, v)
+        x -= lr * m / np.sqrt(vh)
+        assert st["m"][0, 0] == pytest.approx(m, rel=1e-12) and st["vw"][0, 0] == pytest.approx(v, rel=1e-12)
+        assert st["vhw"][0, 0] == pytest.approx(vh, rel=1e-12) and st["x"][0] == pytest.approx(x, rel=1e-10)
+        assert st["e"][0, 0] == 0.0
+
+
+def test_pa_without_compression_averages_per_worker_amsgrad_steps():
+    # Sec. II-A on parameter averaging: with no compression each node takes its own AMSGrad step and the
+    # parameters are averaged.  k = d makes the compressor the identity.
+    o = Oracle("f64")
+    d, n, T = 200, 4, 7
+    b1, b2, lr, eps = 0.9, 0.99, 1e-2, 1e-6
+    rng = np.random.default_rng(8)
+    G = [rng.standard_normal((n, d)) for _ in range(T)]
+    x1 = rng.standard_normal(d)
+    st = init_pa(o, x1, n, eps)
+    hp = inputs.hash_params(3, seed=2)
+    x, m, v, vh = x1.copy(), np.zeros((n, d)), np.full((n, d), eps), np.full((n, d), eps)
+    for g in G:
+        step_pa(o, g, st, hp, 16, d, b1, b2, lr)
+        m = b1 * m + (1 - b1) * g
+        v = b2 * v + (1 - b2) * g * g
+        vh = np.maximum(vh, v)
+        x = np.mean(x[None, :] - lr * m / np.sqrt(vh), axis=0)       # average of the n locally updated copies
+        np.testing.assert_allclose(st["x"], x, rtol=1e-11, atol=1e-13)
+        assert not st["e"].any()
+
+
+def test_pa_auxiliary_sequence_identity_with_decaying_step_size():
+    # Sec. IV-A: x~_{t+1} = x~_t - alpha_t mean_i(m_t^(i)/sqrt(vhat_t^(i))) and x_t - x~_t = alpha_{t-1} e_{t-1};
+    # together with exact recovery (c >= d) the Lemma 1 contraction must hold too.
+    o = Oracle("f64")
+    d, n, k, T, r, c = 1200, 3, 35, 10, 5, 80
+    b1, b2, eps, lr0 = 0.9, 0.99, 1e-6, 1e-2
+    rng = np.random.default_rng(31)
+    G = [rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-2, 0, d) for _ in range(T)]
+    x1 = rng.standard_normal(d)
+    hp = inputs.hash_params(r, seed=9)
+    st = init_pa(o, x1, n, eps)
+    xt, alpha_prev = x1.copy(), None
+    for t in range(1, T + 1):
+        alpha = lr0 / np.sqrt(t)
+        rho = 1.0 if alpha_prev is None else alpha_prev / alpha
+        out = step_pa(o, np.ascontiguousarray(G[t - 1]), st, hp, c, k, b1, b2, alpha, rho)
+        xt = xt - alpha * (st["m"] / np.sqrt(st["vhw"])).mean(axis=0)
+        carried = alpha * st["e"].mean(axis=0)
+        assert np.abs(st["x"] - xt - carried).max() <= 1e-11 * (np.abs(st["x"]).max() + np.abs(carried).max()), t
+        assert not st["e"][:, out["idx"]].any()
+        alpha_prev = alpha
+    # exact recovery: Delta_t is the exact top-k of Delta~_t = mean_i u^(i)  (Lemma 1, deterministic then)
+    st = init_pa(o, x1, n, eps)
+    hp_id = inputs.identity_hash_params(r, seed=9)
+    for t in range(4):
+        out = step_pa(o, np.ascontiguousarray(G[t]), st, hp_id, d, k, b1, b2, lr0)
+        dt = out["u"].mean(axis=0)
+        np.testing.assert_allclose(out["est"], dt, rtol=1e-12, atol=1e-300)
+        full = np.zeros(d)
+        full[out["idx"]] = out["delta"]
+        assert np.sum((full - dt) ** 2) <= (1 - k / d) * np.sum(dt ** 2) * (1 + 1e-12)
+        order = np.lexsort((np.arange(d), -np.abs(dt)))[:k]
+        assert np.array_equal(out["idx"], np.sort(order))
+
+
 def test_plain_unsketch_variant_skips_the_vhat_scaling():
     # Alg. 1 uses the original operator U_0 (no second input): est and Delta carry no 1/sqrt(vhat)
     o = Oracle("f64")
