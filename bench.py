@@ -37,6 +37,7 @@ def kernel_algorithmic_bytes(name, d, n, r, c, k):
         "k_bin_scatter": 4 * n * d,             # reads u once; the staging it writes is not algorithmic
         "k_bin_accumulate": n * rc4,            # writes every table cell once; the staging it reads is not
         "k_sketch_lds": 4 * n * d + n * rc4,
+        "k_head_pa": 36 * n * d,                # g, m, e, v, vhat read; m, u, v, vhat written
         "k_head_scatter": 20 * n * d + 12 * d,  # the head's own traffic; the staging it also writes is not
         "k_bin_lookup": rc4,                    # reads the mean table once
         "k_bin_collect": None,                  # moves only scratch
@@ -93,6 +94,8 @@ def main():
     ap.add_argument("--cpu-sample-d", type=int, default=2_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept resident")
+    ap.add_argument("--variant", choices=["ga", "pa"], default="ga",
+                    help="ga: Alg. 2, gradient averaging (the headline); pa: Alg. 1, parameter averaging")
     ap.add_argument("--overselect", type=int, default=1,
                     help="P of the paper's second round: P*k candidates, then topk_refine (default 1: none)")
     ap.add_argument("--tune", default="fuse_head=1",
@@ -121,20 +124,30 @@ def main():
     idx_f = torch.empty(k, device="cuda", dtype=torch.int32) if P > 1 else b.idx
     delta_f = torch.empty(k, device="cuda") if P > 1 else b.delta
     pool = [gs.step(t) for t in range(max(1, args.pool))]
+    pa = args.variant == "pa"
+    if pa:                                       # Alg. 1: every worker keeps its own second moments
+        v_w = torch.full((n, d), w.eps, device="cuda")
+        vhat_w = torch.full((n, d), w.eps, device="cuda")
+    vh = None if pa else b.vhat
     torch.cuda.synchronize()
+
+    def update(g, idx, delta, k_sel):
+        if pa:
+            ctx.amsgrad_ef_update_pa(g, b.m, b.e_u, v_w, vhat_w, b.x, idx, delta, k_sel, w.beta1, w.beta2, w.lr, 1.0)
+        else:
+            ctx.amsgrad_ef_update(g, b.m, b.e_u, b.v, b.vhat, b.x, idx, delta, k_sel, w.beta1, w.beta2, w.lr, 1.0)
 
     def one_step(t):
         ctx.sketch_accumulate(b.e_u, b.S_workers)
         ctx.sketch_reduce(b.S_workers, b.S_mean)
-        ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
-        ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+        ctx.unsketch_topk(b.S_mean, vh, b.idx, None)
+        ctx.gather_topk(b.e_u, vh, b.idx, b.U_workers, b.delta)
         if P > 1:
             ctx.topk_refine(b.idx, b.delta, k, idx_f, delta_f)
-        ctx.amsgrad_ef_update(pool[(t + 1) % len(pool)], b.m, b.e_u, b.v, b.vhat, b.x, idx_f, delta_f, k,
-                              w.beta1, w.beta2, w.lr, 1.0)
+        update(pool[(t + 1) % len(pool)], idx_f, delta_f, k)
 
     # head of the first iteration, then warm-up
-    ctx.amsgrad_ef_update(pool[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr, 1.0)
+    update(pool[0], None, None, 0)
     t = 0
     for _ in range(args.warmup):
         one_step(t)
@@ -181,7 +194,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: d={d}, n={n} simulated workers, sketch {r}x{c}, k={k}, "
                                f"{w.noise} gradients in {w.nseg} segments + {w.heavy} heavy coordinates",
-                   "d": d, "n": n, "r": r, "c": c, "k": k, "tunables": args.tune, "overselect_P": P},
+                   "d": d, "n": n, "r": r, "c": c, "k": k, "tunables": args.tune, "overselect_P": P, "variant": args.variant},
         "worker_coords_per_s": n * d / (ms_per_step * 1e-3),
         "device_ms_per_step": ev_ms_per_step,
         "step_algorithmic_bytes": step_bytes,
