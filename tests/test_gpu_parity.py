@@ -490,3 +490,64 @@ def test_invalid_arguments_are_rejected_without_launching(sams):
         assert lib.amsgrad_ef_update(ctx._h, None, u.data_ptr(), u.data_ptr(), S.data_ptr(), S.data_ptr(),
                                      S.data_ptr(), None, None, 5, 0.9, 0.99, 1e-3, 1.0) == sams.SAMS_EINVAL
         assert ctx.scratch_bytes >= 4 * 1000
+
+
+def test_step_on_a_side_stream_and_as_a_replayed_hip_graph(sams):
+    """No entry point synchronises the host or allocates, so a whole step can be captured once into a HIP graph on
+    the context's stream and replayed.  Every replay (with eager work and synchronisations in between) must give
+    exactly what the same calls give when issued eagerly."""
+    w = inputs.WORKLOADS["C1"]
+    gs = inputs.GradientStream(w, device="cuda")
+    hp = inputs.hash_params(w.r, seed=w.seed)
+    G = [gs.step(t) for t in range(6)]
+    side = torch.cuda.Stream()
+    for key, val in PATHS["binned-unroll2"].items():       # the order-preserving path: results are reproducible
+        sams.sams_configure(key, val)
+
+    def fresh():
+        with torch.cuda.stream(side):
+            ctx = sams.Context(w.d, w.n, w.r, w.c, w.k, hp, stream=side)
+            b = sams.Buffers(w.d, w.n, w.r, w.c, w.k, w.eps, gs.x1())
+            ctx.amsgrad_ef_update(G[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+        return ctx, b
+
+    def step(ctx, b, g_next):
+        ctx.sketch_accumulate(b.e_u, b.S_workers)
+        ctx.sketch_reduce(b.S_workers, b.S_mean)
+        ctx.unsketch_topk(b.S_mean, b.vhat, b.idx, None)
+        ctx.gather_topk(b.e_u, b.vhat, b.idx, b.U_workers, b.delta)
+        ctx.amsgrad_ef_update(g_next, b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, w.k, w.beta1, w.beta2, w.lr)
+
+    # eager reference on the side stream
+    ctx_e, be = fresh()
+    ref = []
+    with torch.cuda.stream(side):
+        for t in range(5):
+            step(ctx_e, be, G[t + 1])
+            side.synchronize()
+            ref.append((host(be.x).copy(), host(be.idx).copy(), host(be.S_mean).copy()))
+    ctx_e.close()
+    # graph: the gradient of the next iteration is read from a fixed buffer that is refilled between replays
+    ctx_g, bg = fresh()
+    g_in = torch.empty_like(G[0])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        g_in.copy_(G[1])
+        step(ctx_g, bg, g_in)                      # one eager step first (iteration 1)
+        side.synchronize()
+        assert np.array_equal(host(bg.x), ref[0][0])
+        g_in.copy_(G[2])
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(ctx_g, bg, g_in)
+        for t in range(1, 5):                      # capture does not execute: replay iterations 2..5
+            g_in.copy_(G[t + 1])
+            graph.replay()
+            side.synchronize()
+            _ = torch.zeros(1000, device="cuda").sum().item()     # unrelated eager work between replays
+            assert np.array_equal(host(bg.idx), ref[t][1]), t
+            assert np.array_equal(host(bg.x), ref[t][0]), t
+            assert np.array_equal(host(bg.S_mean), ref[t][2]), t
+    ctx_g.close()
+    for key, val in PATHS["default"].items():
+        sams.sams_configure(key, val)
