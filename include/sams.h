@@ -65,9 +65,11 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
 /*
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
- *   "tile_log2"   6..14 (default 14): log2 of the coordinates per tile of the binned sketch path
- *   "win_log2"    0 or 4..15 (default 0): log2 of the buckets per LDS window; tables with c <= 2^win_log2 are
- *                 accumulated row by row in LDS, larger ones through the binned path.  0 = chosen from n, r, c:
+ *   "tile_log2"   0 or 6..14 (default 0): log2 of the coordinates per tile of the binned sketch path.  0 = chosen
+ *                 from d: 2^14, or less (down to 2^8) while the vector has fewer tiles than the chip has
+ *                 compute units
+ *   "win_log2"    0 or 4..15 (default 0): log2 of the buckets per LDS window (the bins of the binned path; a
+ *                 table with c <= 2^win_log2 is a single bin, see "sketch_path").  0 = chosen from n, r, c:
  *                 2^15, or less (down to 2^12) when that is needed to give the chip enough windows to work on
  *   "chunk_log2"  0 or 6..11 (default 0 = 11 for 2^15 windows, else 10): log2 of the stream positions the binned accumulation handles
  *                 between two barriers
@@ -88,7 +90,11 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 registers; with 0 they go through a [r][d] scratch array
  *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
  *                 1: one gather per (row, coordinate) straight from the table
- *   "sketch_path" 0 (default): choose from c as above; 1: one global atomic add per term (no plan memory)
+ *   "sketch_path" 0 (default): the binned, order-preserving path whenever c exceeds one LDS window, and
+ *                 also for smaller tables while d <= 2^22 (one bin; one workgroup per (worker, row) walks the
+ *                 vector); LDS atomics for small tables with larger d; 1: one global atomic add per term
+ *                 (no plan memory); 2: the order-preserving path always; 3: LDS atomics whenever c fits one
+ *                 window
  * Returns SAMS_EINVAL for an unknown key or a value out of range.
  */
 int sams_configure(const char *key, int value);
@@ -136,9 +142,10 @@ int sams_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
  *     S_workers[i][j][h_j(l)] += s_j(l) * u[i][l]      for all workers i, rows j, coordinates l.
  *   u          [n][d] in    the vectors to sketch (what amsgrad_ef_update leaves in e_u)
  *   S_workers  [n][r][c] out, overwritten (zeroed by the call, then accumulated)
- * When c exceeds one LDS window (the binned path) the terms of a bucket are added in ascending
- * coordinate order, i.e. the result equals a sequential loop over l bit for bit and is reproducible.
- * On the other paths (small tables accumulated with LDS atomics, or "sketch_path" = 1) the order is
+ * On the binned path (sams_sketch_mode() == 2: the default unless c fits one LDS window and d > 2^22)
+ * the terms of a bucket are added in ascending coordinate order, i.e. the result equals a sequential
+ * loop over l bit for bit and is reproducible.
+ * On the other paths (LDS atomics, or "sketch_path" = 1) the order is
  * not specified and fp32 rounding may differ from the sequential sum in the last bits; on inputs whose
  * partial sums are exact the result is exact on every path.
  */

@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {14, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 32};
+Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 32};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -121,7 +121,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
         ctx->scratch_bytes += a.bytes;
     }
     int rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
-    if (rc == SAMS_OK && g_tun.sketch_path == 0) rc = plan_create(ctx, g_tun);
+    if (rc == SAMS_OK && g_tun.sketch_path != 1) rc = plan_create(ctx, g_tun);
     if (rc != SAMS_OK) {
         sams_destroy(ctx);
         return rc;
@@ -155,7 +155,7 @@ int sams_configure(const char *key, int value)
 {
     if (!key) return SAMS_EINVAL;
     if (!strcmp(key, "tile_log2")) {
-        if (value < 6 || value > 14) return SAMS_EINVAL;
+        if (value != 0 && (value < 6 || value > 14)) return SAMS_EINVAL;
         g_tun.tile_log2 = value;
     } else if (!strcmp(key, "win_log2")) {
         if (value != 0 && (value < 4 || value > 15)) return SAMS_EINVAL;
@@ -185,7 +185,7 @@ int sams_configure(const char *key, int value)
         if (value != 16 && value != 32) return SAMS_EINVAL;
         g_tun.run_pad = value;
     } else if (!strcmp(key, "sketch_path")) {
-        if (value < 0 || value > 1) return SAMS_EINVAL;
+        if (value < 0 || value > 3) return SAMS_EINVAL;
         g_tun.sketch_path = value;
     } else {
         return SAMS_EINVAL;

@@ -75,11 +75,11 @@ struct Plan {
 
 // process-wide tunables read by sams_create (set through sams_configure)
 struct Tunables {
-    int tile_log2;     // coordinates per tile of the binned path
+    int tile_log2;     // coordinates per tile of the binned path (0 = chosen from d)
     int win_log2;      // buckets per LDS window
     int chunk_log2;    // stream positions between two barriers of the accumulate kernel
     int acc_threads;   // workgroup size of the accumulate kernel
-    int sketch_path;   // 0 = choose from c, 1 = force the global-atomic kernel
+    int sketch_path;   // 0 = choose from c and d, 1 = global atomics, 2 = ordered (binned) always, 3 = LDS atomics when c fits a window
     int scatter_threads;  // workgroup size of the scatter kernel
     int estimate_path;    // 0 = stage 3 through the plan when there is one, 1 = direct gathers from the table
     int fuse_head;        // 1 = amsgrad_ef_update also stages u for the next sketch_accumulate

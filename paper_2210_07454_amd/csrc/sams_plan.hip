@@ -37,6 +37,7 @@ constexpr int kAccDepth = 8;                // chunks in flight per workgroup of
 constexpr int kFusedThreads = 1024;          // kernels whose threads own the same 4-coordinate groups throughout
 constexpr int kFusedIters = 4;              // tiles of at most 2^14 coordinates = 4 float4 per thread
 constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one compute unit; the dynamic-LDS cap of every kernel here
+constexpr int64_t kOrderedSingleBinMaxD = (int64_t)1 << 22;     // largest d sketched in order when c fits one window
 constexpr int kRunPad = 16;                 // slot-group granularity in elements (64 bytes); runs are padded to a multiple of it
 
 constexpr uint16_t kSrcPad = 0x7fffu;          // slot source meaning "padding": tiles hold at most 2^14 coordinates
@@ -803,6 +804,12 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     Plan &pl = ctx->plan;
     pl.win_log2 = tun.win_log2;
     pl.tile_log2 = tun.tile_log2;
+    if (pl.tile_log2 == 0) {
+        // automatic tile: 2^14 coordinates, halved (down to 2^8) while that leaves fewer tiles than compute
+        // units -- one workgroup per tile carries pass 1 and the dense update
+        pl.tile_log2 = 14;
+        while (pl.tile_log2 > 8 && ((ctx->d + ((int64_t)1 << pl.tile_log2) - 1) >> pl.tile_log2) < 256) --pl.tile_log2;
+    }
     if (pl.win_log2 == 0) {
         // automatic window: the largest one (longest runs, least padding) that still leaves about four
         // accumulate workgroups per compute unit (256 units); never more than the table needs
@@ -822,7 +829,11 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.stage_rows = (tun.stage_rows <= 0 || tun.stage_rows > ctx->r) ? ctx->r : tun.stage_rows;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
-    pl.mode = pl.nbins <= 1 ? PLAN_LDS_ROW : PLAN_BINNED;
+    // a table that fits one window: the binned machinery with a single bin keeps the order of the adds (one
+    // workgroup per (worker, row) walks all d coordinates, fine while d is small); LDS atomics over
+    // many workgroups do not, but scale with d
+    const bool ordered_single = tun.sketch_path == 2 || (tun.sketch_path == 0 && ctx->d <= kOrderedSingleBinMaxD);
+    pl.mode = (pl.nbins > 1 || ordered_single) ? PLAN_BINNED : PLAN_LDS_ROW;
     if (pl.mode == PLAN_LDS_ROW) {
         SAMS_HIP(hipFuncSetAttribute((const void *)k_sketch_lds, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
         return SAMS_OK;
