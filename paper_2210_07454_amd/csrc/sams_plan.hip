@@ -545,11 +545,12 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
 __global__ void __launch_bounds__(1024)
 k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta,
              const uint32_t *__restrict__ binbase, float *__restrict__ lk, int64_t c, int win_log2,
-             int64_t nbins, int64_t rowlen, int32_t j0)
+             int64_t nbins, int64_t rowlen, int32_t j0, int32_t nsplit)
 {
     extern __shared__ float win[];
     const int W = 1 << win_log2;
-    const int64_t bin = blockIdx.x;
+    const int64_t bin = blockIdx.x / nsplit;                         // nsplit workgroups share a bin's stream
+    const int64_t part = blockIdx.x % nsplit;
     const int j = j0 + (int)blockIdx.y;
     const int64_t base = bin << win_log2;
     const float *Sj = S_mean + (int64_t)j * c + base;
@@ -561,7 +562,9 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta
     const uint4 *m4 = reinterpret_cast<const uint4 *>(meta + (int64_t)j * rowlen + b0);
     float4 *o4 = reinterpret_cast<float4 *>(lk + (int64_t)blockIdx.y * rowlen + b0);
     const int64_t n4 = (b1 - b0) >> 2;                               // bins are whole chunks: a multiple of 4
-    for (int64_t q = threadIdx.x; q < n4; q += blockDim.x) {
+    const int64_t piece = (n4 + nsplit - 1) / nsplit;
+    const int64_t q1 = (part + 1) * piece < n4 ? (part + 1) * piece : n4;
+    for (int64_t q = part * piece + threadIdx.x; q < q1; q += blockDim.x) {
         const uint4 w = m4[q];
         store_stream(o4 + q, make_float4(win[w.x & wmask], win[w.y & wmask], win[w.z & wmask], win[w.w & wmask]));
     }
@@ -671,6 +674,17 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
 
 constexpr int kFusedMedianMaxRows = 6;      // R * 16 row estimates per thread must stay in registers
 
+// Workgroups per (row, bin) of the lookup: enough of them to give every compute unit a few, while a
+// workgroup still has a good many positions per window it loads.
+static int32_t lookup_split(const Plan &pl, int32_t rows)
+{
+    const int64_t groups = pl.nbins * rows;
+    int64_t nsplit = (1024 + groups - 1) / groups;
+    const int64_t per_bin = pl.rowlen / pl.nbins;                   // about the positions of one bin
+    while (nsplit > 1 && per_bin / nsplit < (int64_t)8 << pl.win_log2) --nsplit;
+    return (int32_t)(nsplit < 1 ? 1 : (nsplit > 64 ? 64 : nsplit));
+}
+
 int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done)
 {
     Plan &pl = ctx->plan;
@@ -680,8 +694,10 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
     float *lk = pl.stg;
     {
         ProfScope ps(ctx, KID_BIN_LOOKUP);
-        hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)pl.nbins, (unsigned)ctx->r), dim3(1024), (size_t)(W * 4),
-                           ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2, pl.nbins, pl.rowlen, 0);
+        const int32_t nsplit = lookup_split(pl, ctx->r);
+        hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)(pl.nbins * nsplit), (unsigned)ctx->r), dim3(1024),
+                           (size_t)(W * 4), ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2,
+                           pl.nbins, pl.rowlen, 0, nsplit);
     }
     {
         ProfScope ps(ctx, KID_BIN_COLLECT);
@@ -711,9 +727,10 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
         const int32_t rj = (ctx->r - j0) < cap ? (ctx->r - j0) : (int32_t)cap;
         {
             ProfScope ps(ctx, KID_BIN_LOOKUP);
-            hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)pl.nbins, (unsigned)rj), dim3(1024), (size_t)(W * 4),
-                               ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2, pl.nbins,
-                               pl.rowlen, j0);
+            const int32_t nsplit = lookup_split(pl, rj);
+            hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)(pl.nbins * nsplit), (unsigned)rj), dim3(1024),
+                               (size_t)(W * 4), ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2,
+                               pl.nbins, pl.rowlen, j0, nsplit);
         }
         {
             ProfScope ps(ctx, KID_BIN_COLLECT);
@@ -811,11 +828,11 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         while (pl.tile_log2 > 8 && ((ctx->d + ((int64_t)1 << pl.tile_log2) - 1) >> pl.tile_log2) < 256) --pl.tile_log2;
     }
     if (pl.win_log2 == 0) {
-        // automatic window: the largest one (longest runs, least padding) that still leaves about four
+        // automatic window: the largest one (longest runs, least padding) that still leaves about eight
         // accumulate workgroups per compute unit (256 units); never more than the table needs
         pl.win_log2 = 15;
         while (pl.win_log2 > 12 &&
-               (int64_t)ctx->n * ctx->r * ((ctx->c + ((int64_t)1 << pl.win_log2) - 1) >> pl.win_log2) < 1024)
+               (int64_t)ctx->n * ctx->r * ((ctx->c + ((int64_t)1 << pl.win_log2) - 1) >> pl.win_log2) < 2048)
             --pl.win_log2;
         while (pl.win_log2 < 15 && ((int64_t)1 << pl.win_log2) < ctx->c &&
                (((int64_t)1 << pl.tile_log2) << pl.win_log2) / ctx->c < 64)
