@@ -64,6 +64,45 @@ __global__ void k_sel_init(SelState *st, uint32_t k, uint32_t *hist)
     }
 }
 
+// The streaming passes of the selection read four consecutive keys per lane with one 16-byte load
+// (the entry points accept 16-byte aligned arrays only; the last, partial group of four is read key by key).  Absent keys
+// (at or beyond len) are reported through the mask `have`.
+struct Keys4 {
+    float v[4];
+    uint32_t have;   // bit z set: v[z] is a key
+};
+__device__ __forceinline__ Keys4 load_keys4(const float *__restrict__ keys, int64_t l, int64_t len)
+{
+    Keys4 q;
+    if (l + 3 < len) {
+        const float4 t = *reinterpret_cast<const float4 *>(keys + l);
+        q.v[0] = t.x; q.v[1] = t.y; q.v[2] = t.z; q.v[3] = t.w;
+        q.have = 0xfu;
+    } else {
+        q.have = 0u;
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+            q.v[z] = (l + z < len) ? keys[l + z] : 0.0f;
+            q.have |= (l + z < len) ? (1u << z) : 0u;
+        }
+    }
+    return q;
+}
+
+// sum over the lanes below this one, and over the whole wavefront, of a per-lane count in 0..7
+__device__ __forceinline__ void wave_prefix3(uint32_t cnt, uint64_t below, uint32_t *excl, uint32_t *total)
+{
+    uint32_t e = 0, t = 0;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const uint64_t m = __ballot((cnt >> b) & 1u);
+        e += (uint32_t)__popcll(m & below) << b;
+        t += (uint32_t)__popcll(m) << b;
+    }
+    *excl = e;
+    *total = t;
+}
+
 // histogram of the current digit over the keys whose higher digits equal the prefix
 __global__ void __launch_bounds__(256)
 k_sel_hist(const float *__restrict__ est, int64_t d, int pass, const SelState *__restrict__ st,
@@ -75,11 +114,15 @@ k_sel_hist(const float *__restrict__ est, int64_t d, int pass, const SelState *_
     const int shift = sel_shift(pass), width = sel_width(pass);
     const uint32_t prefix = st->prefix;
     const uint32_t dmask = (1u << width) - 1u;
-    int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < d; i += stride) {
-        uint32_t key = mag_key(est[i]);
-        if ((key >> (shift + width)) == prefix) atomicAdd(&lh[(key >> shift) & dmask], 1u);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+    for (int64_t l = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) * 4; l < d; l += stride) {
+        const Keys4 q = load_keys4(est, l, d);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+            const uint32_t key = mag_key(q.v[z]);
+            if (((q.have >> z) & 1u) && (key >> (shift + width)) == prefix)
+                atomicAdd(&lh[(key >> shift) & dmask], 1u);
+        }
     }
     __syncthreads();
     for (int t = threadIdx.x; t < kHistBins; t += blockDim.x)
@@ -142,13 +185,21 @@ k_sel_count(const float *__restrict__ est, int64_t d, const SelState *__restrict
     if (tile >= ntile) return;
     const uint32_t tau = st->tau;
     int64_t base = tile * kSelTile;
-    uint32_t ngt = 0, neq = 0;
-    for (int s = 0; s < kSelTile; s += kWave) {
-        int64_t l = base + s + lane;
-        uint32_t key = l < d ? mag_key(est[l]) : 0u;
-        bool gt = l < d && key > tau, eq = l < d && key == tau;
-        ngt += (uint32_t)__popcll(__ballot(gt));
-        neq += (uint32_t)__popcll(__ballot(eq));
+    uint32_t ngt = 0, neq = 0;                                       // this lane's counts
+    for (int s = 0; s < kSelTile; s += kWave * 4) {
+        const Keys4 q = load_keys4(est, base + s + lane * 4, d);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+            const uint32_t key = mag_key(q.v[z]);
+            const bool have = (q.have >> z) & 1u;
+            ngt += (have && key > tau) ? 1u : 0u;
+            neq += (have && key == tau) ? 1u : 0u;
+        }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        ngt += __shfl_xor(ngt, off);
+        neq += __shfl_xor(neq, off);
     }
     if (lane == 0) {
         cnt_gt[tile] = ngt;
@@ -204,23 +255,39 @@ k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict
     int64_t base = tile * kSelTile;
     uint32_t out = sel_base[tile], eqr = eq_base[tile];
     const uint64_t below = ((uint64_t)1 << lane) - 1;
-    for (int s = 0; s < kSelTile; s += kWave) {
-        int64_t l = base + s + lane;
-        float val = l < d ? est[l] : 0.0f;
-        uint32_t key = mag_key(val);
-        bool gt = l < d && key > tau, eq = l < d && key == tau;
-        uint64_t meq = __ballot(eq);
-        bool take = gt || (eq && eqr + (uint32_t)__popcll(meq & below) < k_eq);
-        uint64_t msel = __ballot(take);
-        if (take) {
-            int64_t pos = (int64_t)out + __popcll(msel & below);
-            if (pos < k) {
-                idx[pos] = (int32_t)l;
-                if (est_sel) est_sel[pos] = val;
+    for (int s = 0; s < kSelTile; s += kWave * 4) {
+        const int64_t l0 = base + s + lane * 4;                      // this lane's four consecutive keys
+        const Keys4 q = load_keys4(est, l0, d);
+        uint32_t gt = 0, eq = 0;                                     // bit z: key z is above / at the threshold
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+            const uint32_t key = mag_key(q.v[z]);
+            const bool have = (q.have >> z) & 1u;
+            gt |= (have && key > tau) ? (1u << z) : 0u;
+            eq |= (have && key == tau) ? (1u << z) : 0u;
+        }
+        uint32_t eq_before, eq_total;
+        wave_prefix3((uint32_t)__popc(eq), below, &eq_before, &eq_total);
+        uint32_t take = gt;
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+            const uint32_t rank = eqr + eq_before + (uint32_t)__popc(eq & ((1u << z) - 1u));
+            if (((eq >> z) & 1u) && rank < k_eq) take |= 1u << z;
+        }
+        uint32_t take_before, take_total;
+        wave_prefix3((uint32_t)__popc(take), below, &take_before, &take_total);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+            if ((take >> z) & 1u) {
+                const int64_t pos = (int64_t)out + take_before + __popc(take & ((1u << z) - 1u));
+                if (pos < k) {
+                    idx[pos] = (int32_t)(l0 + z);
+                    if (est_sel) est_sel[pos] = q.v[z];
+                }
             }
         }
-        out += (uint32_t)__popcll(msel);
-        eqr += (uint32_t)__popcll(meq);
+        out += take_total;
+        eqr += eq_total;
     }
 }
 
