@@ -91,16 +91,31 @@ k_head(const float *__restrict__ g, float *__restrict__ m, float *__restrict__ e
 // ------------------------------------------------------------------------------------------
 // stage 2: mean of the worker sketches (Alg. 2, master)
 // ------------------------------------------------------------------------------------------
+// VEC = 4: four consecutive cells per thread with 16-byte loads (needs r*c to be a multiple of 4, so that
+// every worker's table starts on a 16-byte boundary)
+template <int VEC>
 __global__ void __launch_bounds__(256)
 k_reduce(const float *__restrict__ S_w, float *__restrict__ S_mean, int32_t n, int64_t rc)
 {
-    int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    int64_t st = (int64_t)gridDim.x * blockDim.x;
-    float fn = (float)n;
+    int64_t t = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) * VEC;
+    const int64_t st = (int64_t)gridDim.x * blockDim.x * VEC;
+    const float fn = (float)n;
     for (; t < rc; t += st) {
-        float acc = S_w[t];
-        for (int32_t i = 1; i < n; ++i) acc = (acc + S_w[(int64_t)i * rc + t]);
-        S_mean[t] = (acc / fn);
+        if constexpr (VEC == 4) {
+            float4 acc = *reinterpret_cast<const float4 *>(S_w + t);
+            for (int32_t i = 1; i < n; ++i) {
+                const float4 b = *reinterpret_cast<const float4 *>(S_w + (int64_t)i * rc + t);
+                acc.x = (acc.x + b.x);
+                acc.y = (acc.y + b.y);
+                acc.z = (acc.z + b.z);
+                acc.w = (acc.w + b.w);
+            }
+            *reinterpret_cast<float4 *>(S_mean + t) = make_float4((acc.x / fn), (acc.y / fn), (acc.z / fn), (acc.w / fn));
+        } else {
+            float acc = S_w[t];
+            for (int32_t i = 1; i < n; ++i) acc = (acc + S_w[(int64_t)i * rc + t]);
+            S_mean[t] = (acc / fn);
+        }
     }
 }
 
@@ -222,7 +237,10 @@ int enqueue_head(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, 
 int enqueue_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean)
 {
     const int64_t rc = (int64_t)ctx->r * ctx->c;
-    SAMS_LAUNCH(ctx, KID_REDUCE, k_reduce, grid_for(rc, 256, 1 << 16), 256, S_workers, S_mean, ctx->n, rc);
+    if ((rc & 3) == 0)
+        SAMS_LAUNCH(ctx, KID_REDUCE, k_reduce<4>, grid_for(rc / 4, 256, 1 << 16), 256, S_workers, S_mean, ctx->n, rc);
+    else
+        SAMS_LAUNCH(ctx, KID_REDUCE, k_reduce<1>, grid_for(rc, 256, 1 << 16), 256, S_workers, S_mean, ctx->n, rc);
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
 }
