@@ -66,8 +66,8 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
  *   "tile_log2"   0 or 6..14 (default 0): log2 of the coordinates per tile of the binned sketch path.  0 = chosen
- *                 from d: 2^14, or less (down to 2^8) while the vector has fewer tiles than the chip has
- *                 compute units
+ *                 from r and d: 2^14 (2^13 for r > 6, 2^12 for r > 12), or less (down to 2^8) while the vector
+ *                 has fewer tiles than the chip has compute units
  *   "win_log2"    0 or 4..15 (default 0): log2 of the buckets per LDS window (the bins of the binned path; a
  *                 table with c <= 2^win_log2 is a single bin, see "sketch_path").  0 = chosen from n, r, c:
  *                 2^15, or less (down to 2^12) when that is needed to give the chip enough windows to work on
@@ -86,8 +86,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "stage_rows"  0..16 (default 0 = all r rows): rows of the sketch staged at once on the binned path; the
  *                 staging buffer holds 4*n*stage_rows*(1.1 to 1.5)*d bytes and stage 1 runs row group after
  *                 row group (each group after the first re-reads u)
- *   "fuse_median" 1 (default) or 0: with 1 and r <= 6 the plan-driven recovery keeps the row estimates in
- *                 registers; with 0 they go through a [r][d] scratch array
+ *   "fuse_median" 1 (default) or 0: with 1 the plan-driven recovery keeps the row estimates in registers
+ *                 (needs r <= 6 with tiles of 2^14, r <= 12 with 2^13, any r with 2^12 or less); with 0
+ *                 they go through a [r][d] scratch array
  *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
  *                 1: one gather per (row, coordinate) straight from the table
  *   "sketch_path" 0 (default): the binned, order-preserving path whenever c exceeds one LDS window, and

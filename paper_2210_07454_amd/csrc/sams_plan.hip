@@ -609,8 +609,9 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
 }
 
 // k_bin_collect with the median of Sec. II-C and the 1/sqrt(vhat) scaling of Alg. 3 fused in: each thread
-// keeps the R row estimates of its 16 coordinates in registers, so the per-row estimates never go to memory.
-template <int R>
+// keeps the R row estimates of its 4 * ITERS coordinates in registers (tiles of at most 4096 * ITERS
+// coordinates), so the per-row estimates never go to memory.
+template <int R, int ITERS>
 __global__ void __launch_bounds__(kFusedThreads)
 k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ srcp,
                      const uint32_t *__restrict__ dst16, const uint32_t *__restrict__ pbase,
@@ -621,7 +622,7 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
     const int L = 1 << tile_log2;
     const int64_t tile = blockIdx.x;
     const int64_t l0 = tile << tile_log2;
-    float a[R][kFusedIters][4];
+    float a[R][ITERS][4];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         float *buf = rowbuf + (j & 1) * L;
@@ -642,7 +643,7 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
         }
         __syncthreads();   // the other buffer is free again once every thread has passed this barrier
 #pragma unroll
-        for (int it = 0; it < kFusedIters; ++it) {
+        for (int it = 0; it < ITERS; ++it) {
             const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
             float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
             if (p < L) q = *reinterpret_cast<const float4 *>(buf + p);
@@ -650,7 +651,7 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
         }
     }
 #pragma unroll
-    for (int it = 0; it < kFusedIters; ++it) {
+    for (int it = 0; it < ITERS; ++it) {
         const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
         if (p < L && l0 + p < d) {
             float vh[4] = {1.f, 1.f, 1.f, 1.f};
@@ -672,7 +673,19 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
     }
 }
 
-constexpr int kFusedMedianMaxRows = 6;      // R * 16 row estimates per thread must stay in registers
+// R * ITERS * 4 row estimates per thread must stay in registers: up to 6 rows with tiles of 2^14 coordinates,
+// 12 rows with 2^13, 16 rows with 2^12
+static int fused_median_iters(int32_t r, int tile_log2)
+{
+    if (r <= 6 && tile_log2 <= 14) return 4;
+    if (r <= 12 && tile_log2 <= 13) return 2;
+    if (r <= SAMS_MAX_ROWS && tile_log2 <= 12) return 1;
+    return 0;
+}
+// (rows, ITERS) pairs that are instantiated: the ITERS fused_median_iters gives for that many rows
+#define SAMS_FUSED_MEDIAN_VARIANTS(X)                                                              \
+    X(1, 4) X(2, 4) X(3, 4) X(4, 4) X(5, 4) X(6, 4) X(7, 2) X(8, 2) X(9, 2) X(10, 2) X(11, 2) X(12, 2) \
+    X(13, 1) X(14, 1) X(15, 1) X(16, 1)
 
 // Workgroups per (row, bin) of the lookup: enough of them to give every compute unit a few, while a
 // workgroup still has a good many positions per window it loads.
@@ -689,7 +702,8 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
 {
     Plan &pl = ctx->plan;
     *done = false;
-    if (ctx->r > kFusedMedianMaxRows || (ctx->d & 3) != 0 || (int64_t)ctx->n * pl.stage_rows < ctx->r) return SAMS_OK;
+    const int iters = fused_median_iters(ctx->r, pl.tile_log2);
+    if (iters == 0 || (ctx->d & 3) != 0 || (int64_t)ctx->n * pl.stage_rows < ctx->r) return SAMS_OK;
     const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
     float *lk = pl.stg;
     {
@@ -701,14 +715,14 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
     }
     {
         ProfScope ps(ctx, KID_BIN_COLLECT);
-#define SAMS_CM(RR)                                                                                       \
+#define SAMS_CM(RR, IT)                                                                                   \
     case RR:                                                                                              \
-        hipLaunchKernelGGL(k_bin_collect_median<RR>, dim3((unsigned)pl.ntile), dim3(kFusedThreads),       \
+        hipLaunchKernelGGL((k_bin_collect_median<RR, IT>), dim3((unsigned)pl.ntile), dim3(kFusedThreads), \
                            (size_t)(2 * L * 4), ctx->stream, lk, pl.srcp, pl.dst16, pl.pbase, vhat, est,   \
                            ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);                                     \
         break;
         switch (ctx->r) {
-            SAMS_CM(1) SAMS_CM(2) SAMS_CM(3) SAMS_CM(4) SAMS_CM(5) SAMS_CM(6)
+            SAMS_FUSED_MEDIAN_VARIANTS(SAMS_CM)
         }
 #undef SAMS_CM
     }
@@ -822,9 +836,10 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.win_log2 = tun.win_log2;
     pl.tile_log2 = tun.tile_log2;
     if (pl.tile_log2 == 0) {
-        // automatic tile: 2^14 coordinates, halved (down to 2^8) while that leaves fewer tiles than compute
-        // units -- one workgroup per tile carries pass 1 and the dense update
-        pl.tile_log2 = 14;
+        // automatic tile: 2^14 coordinates (2^13 above 6 rows, 2^12 above 12, so that a thread can keep the row
+        // estimates of its coordinates in registers for the median), halved (down to 2^8) while that leaves fewer
+        // tiles than compute units -- one workgroup per tile carries pass 1 and the dense update
+        pl.tile_log2 = ctx->r <= 6 ? 14 : (ctx->r <= 12 ? 13 : 12);
         while (pl.tile_log2 > 8 && ((ctx->d + ((int64_t)1 << pl.tile_log2) - 1) >> pl.tile_log2) < 256) --pl.tile_log2;
     }
     if (pl.win_log2 == 0) {
@@ -884,11 +899,11 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-#define SAMS_CM(RR)                                                                                \
+#define SAMS_CM(RR, IT)                                                                            \
     if (e == hipSuccess)                                                                           \
-        e = hipFuncSetAttribute((const void *)k_bin_collect_median<RR>,                            \
+        e = hipFuncSetAttribute((const void *)k_bin_collect_median<RR, IT>,                        \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-        SAMS_CM(1) SAMS_CM(2) SAMS_CM(3) SAMS_CM(4) SAMS_CM(5) SAMS_CM(6)
+        SAMS_FUSED_MEDIAN_VARIANTS(SAMS_CM)
 #undef SAMS_CM
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_lookup, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
