@@ -70,7 +70,9 @@ struct Plan {
     uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags
     float *stg;         // [n][r][rowlen]       per-step staging: signed values at their stream positions
     const float *staged_u;  // vector whose sorted copy the staging holds (set by a fused head), else null
-    float *rowest;      // [r][d]               per-step: signed row estimates in coordinate order (stage 3)
+    float *rowest;      // [r][d]               per-step: signed row estimates in coordinate order (stage 3);
+                        //                      absent when the median is fused (fused_median)
+    bool fused_median;  // stage 3 keeps the row estimates in registers (decided when the plan is built)
 };
 
 // process-wide tunables read by sams_create (set through sams_configure)
@@ -83,7 +85,7 @@ struct Tunables {
     int scatter_threads;  // workgroup size of the scatter kernel
     int estimate_path;    // 0 = stage 3 through the plan when there is one, 1 = direct gathers from the table
     int fuse_head;        // 1 = amsgrad_ef_update also stages u for the next sketch_accumulate
-    int fuse_median;      // 1 = recovery keeps the row estimates in registers (r <= 6), 0 = through memory
+    int fuse_median;      // 1 = recovery keeps the row estimates in registers where the shape allows, 0 = through memory
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats
     int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
 };

@@ -702,8 +702,7 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
 {
     Plan &pl = ctx->plan;
     *done = false;
-    const int iters = fused_median_iters(ctx->r, pl.tile_log2);
-    if (iters == 0 || (ctx->d & 3) != 0 || (int64_t)ctx->n * pl.stage_rows < ctx->r) return SAMS_OK;
+    if (!pl.fused_median) return SAMS_OK;
     const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
     float *lk = pl.stg;
     {
@@ -955,7 +954,11 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen / kRunPad) * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * pl.stage_rows * rowlen * 4);
-        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.rowest, r * ctx->d * 4);
+        // the median is fused when a thread can hold the row estimates of its coordinates and the staging
+        // buffer can hold the looked-up values of all r rows; otherwise they go through rowest
+        pl.fused_median = tun.fuse_median && fused_median_iters(ctx->r, pl.tile_log2) > 0 && (ctx->d & 3) == 0 &&
+                          n * pl.stage_rows >= r;
+        if (rc == SAMS_OK && !pl.fused_median) rc = dev_alloc(ctx, (void **)&pl.rowest, r * ctx->d * 4);
         if (rc != SAMS_OK) break;
         e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess)

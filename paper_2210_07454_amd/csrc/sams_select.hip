@@ -297,7 +297,7 @@ int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, floa
     const int grid = grid_for(ctx->d, block);
     if (ctx->plan.mode == PLAN_BINNED && g_tun.estimate_path == 0) {
         bool done = false;
-        if (g_tun.fuse_median) SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done));
+        SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done));
         if (done) return SAMS_OK;
         SAMS_TRY(enqueue_row_estimates_planned(ctx, S_mean, ctx->plan.rowest));
         switch (ctx->r) {
