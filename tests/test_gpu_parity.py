@@ -395,6 +395,19 @@ def test_chained_steps_follow_the_oracle(sams, path, wl, d, steps):
     """Free-running GPU run; at every step the oracle is restarted from the GPU's previous state, so
     each step is compared on real evolving state (bitmap of I_{t-1}, error feedback, vhat)."""
     w = inputs.WORKLOADS[wl].scaled(d)
+    run_chain(sams, w, steps, lambda t: w.lr)
+
+
+@pytest.mark.parametrize("wl,d,steps", [("C1", 65_536, 8), ("P2a", 60_000, 5), ("C4", 300_000, 4)])
+def test_chained_steps_with_a_decaying_step_size(sams, wl, d, steps):
+    """alpha_t = alpha / sqrt(t): the error feedback enters with the ratio alpha_{t-1} / alpha_t != 1
+    (worker line of Alg. 2) and x moves by alpha_t Delta_t."""
+    w = inputs.WORKLOADS[wl].scaled(d)
+    run_chain(sams, w, steps, lambda t: w.lr / np.sqrt(t))
+
+
+def run_chain(sams, w, steps, alpha):
+    """alpha(t) = step size of iteration t = 1, 2, ..."""
     gs = inputs.GradientStream(w, device="cuda")
     hp = inputs.hash_params(w.r, seed=w.seed)
     o = Oracle("f32")
@@ -404,11 +417,13 @@ def test_chained_steps_follow_the_oracle(sams, path, wl, d, steps):
         prev_mask = np.zeros(w.d, np.uint8)
         st = dict(m=np.zeros((w.n, w.d), np.float32), e=np.zeros((w.n, w.d), np.float32),
                   v=np.full(w.d, w.eps, np.float32), vhat=np.full(w.d, w.eps, np.float32), x=host(b.x).copy())
-        ctx.amsgrad_ef_update(G[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+        ctx.amsgrad_ef_update(G[0], b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, w.beta1, w.beta2, alpha(1))
         n_diff = 0
-        for t in range(steps):
-            # oracle: head of step t from the state the GPU had before its head
-            o.head(host(G[t]), st["m"], st["e"], st["v"], st["vhat"], prev_mask if t else None, w.beta1, w.beta2)
+        for t in range(steps):                                        # iteration t + 1 of the paper
+            # oracle: head of this iteration from the state the GPU had before its head
+            rho = np.float32(alpha(t) / alpha(t + 1)) if t else np.float32(1.0)
+            o.head(host(G[t]), st["m"], st["e"], st["v"], st["vhat"], prev_mask if t else None, w.beta1, w.beta2,
+                   rho=float(rho))
             got = gpu_state(b)
             for key in ("m", "e", "v", "vhat", "x"):
                 assert np.array_equal(got[key], st[key]), (t, key)
@@ -437,8 +452,10 @@ def test_chained_steps_follow_the_oracle(sams, path, wl, d, steps):
             assert np.array_equal(host(b.U_workers), U_w) and np.array_equal(host(b.delta), delta), t
             # tail of t (+ head of t+1) on the GPU; the oracle's tail here, its head at the loop top
             g_next = G[t + 1] if t + 1 < steps else None
-            ctx.amsgrad_ef_update(g_next, b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, w.k, w.beta1, w.beta2, w.lr)
-            o.tail(st["e"], st["x"], idx, delta, w.lr)
+            lr_t = float(np.float32(alpha(t + 1)))
+            ctx.amsgrad_ef_update(g_next, b.m, b.e_u, b.v, b.vhat, b.x, b.idx, b.delta, w.k, w.beta1, w.beta2, lr_t,
+                                  ef_ratio=float(np.float32(alpha(t + 1) / alpha(t + 2))))
+            o.tail(st["e"], st["x"], idx, delta, lr_t)
             prev_mask = np.zeros(w.d, np.uint8)
             prev_mask[idx] = 1
         got = gpu_state(b)
