@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C4")
-    ap.add_argument("--cpu-sample-d", type=int, default=8_000_000)
+    ap.add_argument("--cpu-sample-d", type=int, default=30_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept resident")
     ap.add_argument("--variant", choices=["ga", "pa"], default="ga",
