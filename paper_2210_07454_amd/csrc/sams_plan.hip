@@ -473,57 +473,59 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     const uint32_t *m = meta + (int64_t)j * rowlen + b0;
     const int64_t nchunk = (b1 - b0) / CH;
     const uint32_t wmask = (uint32_t)W - 1u;
-    // register ring of kAccDepth chunks: the loads of chunk q + kAccDepth are issued while chunk q is processed
+    // Register ring of kAccDepth chunks: once chunk q has been processed its registers receive chunk
+    // q + kAccDepth.  Every load of the ring is issued unconditionally and in a fixed order (past the end of the
+    // bin the last chunk is read again, which costs no HBM traffic; the scheduling barriers keep the groups in
+    // program order), and straight into the registers the loop carries: the compiler can then wait for exactly
+    // the oldest group, with kAccDepth - 1 younger groups still in flight.  With loads under a condition, or
+    // into temporaries copied at the loop end, it waits for all of them.
     float rv[kAccDepth][UNROLL];
     uint32_t rm[kAccDepth][UNROLL];
-#pragma unroll
-    for (int s = 0; s < kAccDepth; ++s) {
-        if (s < nchunk) {
-#pragma unroll
-            for (int z = 0; z < UNROLL; ++z) {
-                rv[s][z] = __builtin_nontemporal_load(v + (int64_t)s * CH + z * THREADS + threadIdx.x);
-                rm[s][z] = m[(int64_t)s * CH + z * THREADS + threadIdx.x];
-            }
-        }
-    }
-    for (int64_t q0 = 0; q0 < nchunk; q0 += kAccDepth) {
+    if (nchunk > 0) {                                                // uniform over the workgroup
+        const int64_t last = nchunk - 1;
 #pragma unroll
         for (int s = 0; s < kAccDepth; ++s) {
-            const int64_t q = q0 + s;
-            if (q < nchunk) {                                        // uniform over the workgroup
-                float cv[UNROLL];
-                uint32_t cm[UNROLL];
+            const int64_t qs = s < last ? s : last;
 #pragma unroll
-                for (int z = 0; z < UNROLL; ++z) {
-                    cv[z] = rv[s][z];
-                    cm[z] = rm[s][z];
-                }
-                if (q + kAccDepth < nchunk) {
+            for (int z = 0; z < UNROLL; ++z) {
+                rv[s][z] = __builtin_nontemporal_load(v + qs * CH + z * THREADS + threadIdx.x);
+                rm[s][z] = m[qs * CH + z * THREADS + threadIdx.x];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (int64_t q0 = 0; q0 < nchunk; q0 += kAccDepth) {
+#pragma unroll
+            for (int s = 0; s < kAccDepth; ++s) {
+                const int64_t q = q0 + s;
+                if (q < nchunk) {                                    // uniform over the workgroup
+                    uint2 *xb = xbuf + (q & 1) * CH;
+#pragma unroll
+                    for (int z = 0; z < UNROLL; ++z)
+                        xb[z * THREADS + threadIdx.x] = make_uint2(__float_as_uint(rv[s][z]), rm[s][z]);
+                    __syncthreads();   // also orders the previous chunk's window updates before this chunk's
 #pragma unroll
                     for (int z = 0; z < UNROLL; ++z) {
-                        rv[s][z] = __builtin_nontemporal_load(v + (q + kAccDepth) * CH + z * THREADS + threadIdx.x);
-                        rm[s][z] = m[(q + kAccDepth) * CH + z * THREADS + threadIdx.x];
+                        uint32_t word = rm[s][z];
+                        if (!(word & kMetaNotFirst)) {
+                            const uint32_t w = word & wmask;
+                            float x = win[w] + rv[s][z];
+                            while (word & kMetaHasNext) {
+                                uint2 e = xb[(word >> kMetaNextShift) & (CH - 1)];
+                                x = x + __uint_as_float(e.x);
+                                word = e.y;
+                            }
+                            win[w] = x;
+                        }
                     }
                 }
-                uint2 *xb = xbuf + (q & 1) * CH;
-#pragma unroll
-                for (int z = 0; z < UNROLL; ++z)
-                    xb[z * THREADS + threadIdx.x] = make_uint2(__float_as_uint(cv[z]), cm[z]);
-                __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+                __builtin_amdgcn_sched_barrier(0);
+                const int64_t qn = (q + kAccDepth) < last ? (q + kAccDepth) : last;
 #pragma unroll
                 for (int z = 0; z < UNROLL; ++z) {
-                    uint32_t word = cm[z];
-                    if (!(word & kMetaNotFirst)) {
-                        const uint32_t w = word & wmask;
-                        float x = win[w] + cv[z];
-                        while (word & kMetaHasNext) {
-                            uint2 e = xb[(word >> kMetaNextShift) & (CH - 1)];
-                            x = x + __uint_as_float(e.x);
-                            word = e.y;
-                        }
-                        win[w] = x;
-                    }
+                    rv[s][z] = __builtin_nontemporal_load(v + qn * CH + z * THREADS + threadIdx.x);
+                    rm[s][z] = m[qn * CH + z * THREADS + threadIdx.x];
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
