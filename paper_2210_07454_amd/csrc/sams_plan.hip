@@ -45,22 +45,18 @@ constexpr uint32_t kMetaNextShift = 15;
 constexpr uint32_t kMetaHasNext = 1u << 26;
 constexpr uint32_t kMetaNotFirst = 1u << 27;   // padding, or a position some earlier position adds
 
-// streaming accesses: data touched once per step should not push the shared metadata out of L2
+// streaming accesses: data touched once per step should not push the shared metadata out of L2.
+// One 16-byte nontemporal instruction each (the pointers are 16-byte aligned, as float4 requires).
+typedef float vec4f __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void store_stream(float4 *p, const float4 &v)
 {
-    __builtin_nontemporal_store(v.x, &p->x);
-    __builtin_nontemporal_store(v.y, &p->y);
-    __builtin_nontemporal_store(v.z, &p->z);
-    __builtin_nontemporal_store(v.w, &p->w);
+    vec4f t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<vec4f *>(p));
 }
 __device__ __forceinline__ float4 load_stream(const float4 *p)
 {
-    float4 v;
-    v.x = __builtin_nontemporal_load(&p->x);
-    v.y = __builtin_nontemporal_load(&p->y);
-    v.z = __builtin_nontemporal_load(&p->z);
-    v.w = __builtin_nontemporal_load(&p->w);
-    return v;
+    const vec4f t = __builtin_nontemporal_load(reinterpret_cast<const vec4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
 }
 
 // Rows [j0, j0 + rj) of the r rows are handled by one launch; their staging is stg[n][sr][rowlen] with
