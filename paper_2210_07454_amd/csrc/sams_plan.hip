@@ -195,7 +195,7 @@ k_plan_place(HashParams hp, int pad, int tile_log2, int win_log2, int64_t nbins,
              int64_t rowlen, const uint16_t *__restrict__ src, const uint16_t *__restrict__ bst,
              const uint32_t *__restrict__ off, const uint32_t *__restrict__ binbase,
              const uint32_t *__restrict__ pbase, uint16_t *__restrict__ srcp, uint32_t *__restrict__ dst16,
-             uint32_t *__restrict__ meta)
+             uint32_t *__restrict__ meta, uint16_t *__restrict__ wlow)
 {
     extern __shared__ uint32_t pst[];                               // [nbins + 1] padded prefix inside the tile
     __shared__ uint32_t part[256];
@@ -236,6 +236,7 @@ k_plan_place(HashParams hp, int pad, int tile_log2, int win_log2, int64_t nbins,
                 sv = sj[a + s];
                 uint32_t wl = bucket_of(hp, j, (uint32_t)(l0 + (sv & 0x7fffu))) & wmask;
                 meta[(int64_t)j * rowlen + start + s] = wl;
+                wlow[(int64_t)j * rowlen + start + s] = (uint16_t)wl;
             }
             srcp[(int64_t)j * rowlen + po + s] = sv;
             if ((s & (kRunPad - 1)) == 0) dst16[((int64_t)j * rowlen + po + s) / kRunPad] = start + (uint32_t)s;
@@ -541,7 +542,7 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
 // gives one workgroup per tile, which brings the values of its slots back into coordinate order through
 // LDS, applies the signs, and writes rowest[row][l] = s_row(l) * S[row][h_row(l)] (contiguous).
 __global__ void __launch_bounds__(1024)
-k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta,
+k_bin_lookup(const float *__restrict__ S_mean, const uint16_t *__restrict__ wlow,
              const uint32_t *__restrict__ binbase, float *__restrict__ lk, int64_t c, int win_log2,
              int64_t nbins, int64_t rowlen, int32_t j0, int32_t nsplit)
 {
@@ -555,16 +556,17 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint32_t *__restrict__ meta
     const int64_t lim = (c - base) < W ? (c - base) : W;
     for (int t = threadIdx.x; t < W; t += blockDim.x) win[t] = t < lim ? Sj[t] : 0.f;
     __syncthreads();
-    const uint32_t wmask = (uint32_t)W - 1u;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
-    const uint4 *m4 = reinterpret_cast<const uint4 *>(meta + (int64_t)j * rowlen + b0);
+    // 4 positions per thread and step: their 2-byte buckets in one 8-byte load, one 16-byte store; a wavefront
+    // reads and writes whole lines (bins start and end on multiples of the chunk, at least 64 positions)
+    const uint2 *m4 = reinterpret_cast<const uint2 *>(wlow + (int64_t)j * rowlen + b0);
     float4 *o4 = reinterpret_cast<float4 *>(lk + (int64_t)blockIdx.y * rowlen + b0);
-    const int64_t n4 = (b1 - b0) >> 2;                               // bins are whole chunks: a multiple of 4
+    const int64_t n4 = (b1 - b0) >> 2;
     const int64_t piece = (n4 + nsplit - 1) / nsplit;
     const int64_t q1 = (part + 1) * piece < n4 ? (part + 1) * piece : n4;
     for (int64_t q = part * piece + threadIdx.x; q < q1; q += blockDim.x) {
-        const uint4 w = m4[q];
-        store_stream(o4 + q, make_float4(win[w.x & wmask], win[w.y & wmask], win[w.z & wmask], win[w.w & wmask]));
+        const uint2 w = m4[q];
+        store_stream(o4 + q, make_float4(win[w.x & 0xffffu], win[w.x >> 16], win[w.y & 0xffffu], win[w.y >> 16]));
     }
 }
 
@@ -707,7 +709,7 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
         ProfScope ps(ctx, KID_BIN_LOOKUP);
         const int32_t nsplit = lookup_split(pl, ctx->r);
         hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)(pl.nbins * nsplit), (unsigned)ctx->r), dim3(1024),
-                           (size_t)(W * 4), ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2,
+                           (size_t)(W * 4), ctx->stream, S_mean, pl.wlow, pl.binbase, lk, ctx->c, pl.win_log2,
                            pl.nbins, pl.rowlen, 0, nsplit);
     }
     {
@@ -740,7 +742,7 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
             ProfScope ps(ctx, KID_BIN_LOOKUP);
             const int32_t nsplit = lookup_split(pl, rj);
             hipLaunchKernelGGL(k_bin_lookup, dim3((unsigned)(pl.nbins * nsplit), (unsigned)rj), dim3(1024),
-                               (size_t)(W * 4), ctx->stream, S_mean, pl.meta, pl.binbase, lk, ctx->c, pl.win_log2,
+                               (size_t)(W * 4), ctx->stream, S_mean, pl.wlow, pl.binbase, lk, ctx->c, pl.win_log2,
                                pl.nbins, pl.rowlen, j0, nsplit);
         }
         {
@@ -951,6 +953,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         rc = dev_alloc(ctx, (void **)&pl.srcp, r * rowlen * 2);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen / kRunPad) * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.wlow, r * rowlen * 2);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * pl.stage_rows * rowlen * 4);
         // the median is fused when a thread can hold the row estimates of its coordinates and the staging
         // buffer can hold the looked-up values of all r rows; otherwise they go through rowest
@@ -963,13 +966,14 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
             e = hipMemcpyAsync(pl.pbase, h_tile, (size_t)(r * (pl.ntile + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         rc = enqueue_fill_u32(ctx, pl.meta, r * rowlen, kMetaNotFirst);
+        if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, reinterpret_cast<uint32_t *>(pl.wlow), r * rowlen / 2, 0u);   // padding: bucket 0
         if (rc != SAMS_OK) break;
         {
             ProfScope ps(ctx, KID_PLAN_BUILD);
             hipLaunchKernelGGL(k_plan_place, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256),
                                (size_t)((NB + 1) * 4), ctx->stream, ctx->hp, pl.run_pad, pl.tile_log2, pl.win_log2, NB,
                                pl.ntile, pl.dpad, rowlen, src, bst, off, pl.binbase, pl.pbase, pl.srcp, pl.dst16,
-                               pl.meta);
+                               pl.meta, pl.wlow);
             hipLaunchKernelGGL(k_plan_chain, dim3((unsigned)(rowlen / CH), (unsigned)r),
                                dim3(CH < kPlanThreads ? (unsigned)CH : kPlanThreads), (size_t)(CH * 4), ctx->stream,
                                pl.chunk_log2, rowlen, pl.meta);
@@ -989,11 +993,12 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
 void plan_destroy(sams_ctx *ctx)
 {
     Plan &pl = ctx->plan;
-    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.stg, pl.rowest};
+    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.wlow, pl.stg, pl.rowest};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     pl.srcp = nullptr;
     pl.dst16 = pl.pbase = pl.binbase = pl.meta = nullptr;
+    pl.wlow = nullptr;
     pl.stg = pl.rowest = nullptr;
 }
 
