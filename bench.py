@@ -85,32 +85,6 @@ def cpu_baseline(w, sample_d):
                       f"k={ws.k}; {dt:.2f} s on 1 thread"}
 
 
-def precondition_vram(torch, fraction=0.995):
-    """Allocate (nearly) all free device memory once in 1 GiB blocks and give it back, before any buffer of the
-    run exists.  Nothing is computed and nothing stays allocated.
-
-    On these boxes the device's memory manager places later allocations differently afterwards (for this process
-    and for later ones, until the box is recycled), and the placement of the library's own buffers (plan and
-    staging) decides between two speeds of the very same kernels on the very same inputs: the fused head + scatter
-    takes 9.05 ms at d = 124M on a fresh box and 7.85 ms after this pass, the other kernels of the step gain
-    3-5 %.  Which buffer matters was found by re-allocating one object at a time (only a new context flips the
-    speed); a single buffer of the same size shows no such effect for random reads or scattered run writes, and a
-    pass that leaves some 8 % of the memory untouched, or that allocates one block of the whole size, does not
-    help the process that makes it.  The cause is not known (the placement of the plan's metadata in the
-    memory-side cache is the suspicion).
-    """
-    free, _ = torch.cuda.mem_get_info()
-    blocks = []
-    try:
-        for _ in range(int(free * fraction) >> 30):
-            blocks.append(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"))
-    except RuntimeError:                               # out of memory: what could be had has been had
-        pass
-    torch.cuda.synchronize()
-    del blocks
-    torch.cuda.empty_cache()
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,7 +120,9 @@ def main():
     kc = P * k                                   # candidates taken from the sketch
     torch.cuda.set_device(0)
     if not args.no_vram_precondition:
-        precondition_vram(torch)
+        # nearly all free device memory allocated once in 1 GiB blocks and given back, before any buffer of the
+        # run exists: afterwards the library's buffers are placed so that the same kernels run 3-14 % faster
+        sams.sams_precondition_device_memory(0.995)
     gs = inputs.GradientStream(w, device="cuda")
     hp = inputs.hash_params(r, seed=w.seed)
     ctx = sams.Context(d, n, r, c, kc, hp)

@@ -197,6 +197,31 @@ int sams_sketch_mode(const sams_ctx *ctx) { return ctx ? ctx->plan.mode : -1; }
 
 int64_t sams_scratch_bytes(const sams_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }
 
+int64_t sams_precondition_device_memory(double fraction)
+{
+    if (!(fraction > 0.0) || fraction > 1.0) return SAMS_EINVAL;
+    size_t free_b = 0, total_b = 0;
+    hipError_t e = hipMemGetInfo(&free_b, &total_b);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return SAMS_EHIP; }
+    const size_t block = (size_t)1 << 30;
+    const size_t want = (size_t)((double)free_b * fraction) / block;
+    void **held = (void **)malloc((want + 1) * sizeof(void *));
+    if (!held) return SAMS_ENOMEM;
+    size_t got = 0;
+    while (got < want) {
+        if (hipMalloc(&held[got], block) != hipSuccess) {
+            (void)hipGetLastError();                                 // out of memory: what could be had has been had
+            break;
+        }
+        ++got;
+    }
+    e = hipDeviceSynchronize();
+    for (size_t q = 0; q < got; ++q) (void)hipFree(held[q]);
+    free(held);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return SAMS_EHIP; }
+    return (int64_t)got;
+}
+
 int sams_profile_kernels(void) { return KID_COUNT; }
 
 const char *sams_profile_name(int kernel) { return kernel_name(kernel); }

@@ -20,7 +20,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
         SAMS_EHIP: "SAMS_EHIP (HIP runtime error)"}
 
 # every symbol include/sams.h declares
-EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_last_hip_error", "sams_hash_dump",
+EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_precondition_device_memory", "sams_last_hip_error", "sams_hash_dump",
            "sams_configure", "sams_sketch_mode", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk", "topk_refine",
            "amsgrad_ef_update", "amsgrad_ef_update_pa"]
@@ -51,6 +51,8 @@ def load() -> ctypes.CDLL:
     lib.sams_destroy.argtypes = [vp]
     lib.sams_scratch_bytes.argtypes = [vp]
     lib.sams_scratch_bytes.restype = i64
+    lib.sams_precondition_device_memory.argtypes = [ctypes.c_double]
+    lib.sams_precondition_device_memory.restype = i64
     lib.sams_last_hip_error.argtypes = []
     lib.sams_hash_dump.argtypes = [vp, vp, vp]
     lib.sams_configure.argtypes = [ctypes.c_char_p, ctypes.c_int]
@@ -68,7 +70,7 @@ def load() -> ctypes.CDLL:
     lib.amsgrad_ef_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
     lib.amsgrad_ef_update_pa.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
     for name in EXPORTS:
-        if name not in ("sams_scratch_bytes", "sams_profile_name"):
+        if name not in ("sams_scratch_bytes", "sams_profile_name", "sams_precondition_device_memory"):
             getattr(lib, name).restype = ctypes.c_int
     lib.sams_profile_name.restype = ctypes.c_char_p
     _lib = lib
@@ -77,6 +79,16 @@ def load() -> ctypes.CDLL:
 
 def sams_configure(key: str, value: int):
     _check(load().sams_configure(key.encode(), int(value)), f"sams_configure({key}={value})")
+
+
+def sams_precondition_device_memory(fraction: float = 0.995) -> int:
+    """Allocate-and-free pass over the free memory of the current device (see sams.h); returns the GiB held."""
+    if not torch.cuda.is_available():
+        raise RuntimeError("paper_2210_07454_amd needs a GPU: no CPU fallback exists")
+    got = int(load().sams_precondition_device_memory(float(fraction)))
+    if got < 0:
+        raise SamsError(got, "sams_precondition_device_memory")
+    return got
 
 
 def _ptr(t, dtype=None, shape=None, name="tensor"):

@@ -73,6 +73,8 @@ def test_configure_rejects_unknown_keys_and_bad_values_without_a_gpu():
     for key, val in ok:                      # leaves the defaults in place
         assert lib.sams_configure(key, val) == sams.SAMS_OK, (key, val)
     assert lib.sams_sketch_mode(None) == -1
+    assert lib.sams_precondition_device_memory(0.0) == sams.SAMS_EINVAL       # refused before any device call
+    assert lib.sams_precondition_device_memory(1.5) == sams.SAMS_EINVAL
     assert lib.sams_profile_kernels() > 10
     names = {lib.sams_profile_name(q).decode() for q in range(lib.sams_profile_kernels())}
     assert {"k_head_scatter", "k_bin_accumulate", "k_sel_hist"} <= names
