@@ -21,14 +21,16 @@ import time
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def step_algorithmic_bytes(d, n, r, c, k):
+def step_algorithmic_bytes(d, n, r, c, k, pa=False):
     """Bytes the method itself must move per step: g read, m and e read+written (20nd); v read+written,
-    vhat read (12d); worker tables written once and read once, mean table written once and read once
-    ((2n+2)rc*4); sparse second round and update (k(8n+24))."""
-    return 20 * n * d + 12 * d + (2 * n + 2) * r * c * 4 + k * (8 * n + 24)
+    vhat read (12d) -- with parameter averaging v and vhat are per worker, read and written (16nd instead);
+    worker tables written once and read once, mean table written once and read once ((2n+2)rc*4); sparse
+    second round and update (k(8n+24))."""
+    dense = 36 * n * d if pa else 20 * n * d + 12 * d
+    return dense + (2 * n + 2) * r * c * 4 + k * (8 * n + 24)
 
 
-def kernel_algorithmic_bytes(name, d, n, r, c, k):
+def kernel_algorithmic_bytes(name, d, n, r, c, k, pa=False):
     """Compulsory traffic of one launch of a kernel: its inputs read once plus its outputs written once."""
     rc4 = r * c * 4
     table = {
@@ -38,7 +40,8 @@ def kernel_algorithmic_bytes(name, d, n, r, c, k):
         "k_bin_accumulate": n * rc4,            # writes every table cell once; the staging it reads is not
         "k_sketch_lds": 4 * n * d + n * rc4,
         "k_head_pa": 36 * n * d,                # g, m, e, v, vhat read; m, u, v, vhat written
-        "k_head_scatter": 20 * n * d + 12 * d,  # the head's own traffic; the staging it also writes is not
+        # the head's own traffic; the staging it also writes is not
+        "k_head_scatter": 36 * n * d if pa else 20 * n * d + 12 * d,
         "k_bin_lookup": rc4,                    # reads the mean table once
         "k_bin_collect": None,                  # moves only scratch
         "k_est_median": 4 * d + 4 * d,          # vhat read, estimates written
@@ -180,14 +183,14 @@ def main():
     dom = max(prof.items(), key=lambda kv: kv[1][0])
     dom_name, (dom_ms, dom_n) = dom
     avg_ms = dom_ms / dom_n
-    kbytes = kernel_algorithmic_bytes(dom_name, d, n, r, c, k)
+    kbytes = kernel_algorithmic_bytes(dom_name, d, n, r, c, k, pa)
     achieved = (kbytes / (avg_ms * 1e-3)) / 1e9 if kbytes else None
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                "traffic": load_traffic(dom_name, args.workload),
+                "traffic": None if (pa or P > 1) else load_traffic(dom_name, args.workload),   # measured for the default variant
                 "algorithmic_bytes_per_launch": kbytes, "avg_launch_ms": avg_ms,
                 "launches_per_step": dom_n / args.steps}
-    step_bytes = step_algorithmic_bytes(d, n, r, c, k)
+    step_bytes = step_algorithmic_bytes(d, n, r, c, k, pa)
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     out = {

@@ -319,7 +319,7 @@ int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, 
     SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
     if (g_next) {
         if (head_can_fuse(ctx))
-            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
+            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio, false));
         else
             SAMS_TRY(enqueue_head(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
     }
@@ -337,7 +337,12 @@ int amsgrad_ef_update_pa(sams_ctx *ctx, const float *g_next, float *m, float *e_
         return SAMS_EINVAL;
     ctx->plan.staged_u = nullptr;                                    // e_u is about to change
     SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
-    if (g_next) SAMS_TRY(enqueue_head_pa(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio));
+    if (g_next) {
+        if (head_can_fuse(ctx))
+            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio, true));
+        else
+            SAMS_TRY(enqueue_head_pa(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio));
+    }
     return SAMS_OK;
 }
 

@@ -196,7 +196,7 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
 int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done);
 bool head_can_fuse(const sams_ctx *ctx);
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
-                         float beta1, float beta2, float rho);
+                         float beta1, float beta2, float rho, bool pa);   // pa: v, vhat are [n][d] (Alg. 1)
 // sams_select.hip
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
 int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel);

@@ -352,6 +352,8 @@ struct HeadArgs {
     float beta1, omb1, beta2, omb2, rho;
 };
 
+// PA: the head of Alg. 1 instead (every worker keeps its own v, vhat [n][d]; u = m / sqrt(vhat) + rho e).
+template <bool PA>
 __global__ void __launch_bounds__(kFusedThreads)
 k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
                const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
@@ -385,13 +387,31 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
                     const float gv[4] = {a.x, a.y, a.z, a.w}, mv[4] = {b.x, b.y, b.z, b.w},
                                 ev[4] = {cc.x, cc.y, cc.z, cc.w};
                     float mo[4];
+                    if constexpr (PA) {
+                        const float4 pv = load_stream(reinterpret_cast<const float4 *>(ha.v + wbase + p));
+                        const float4 ph = load_stream(reinterpret_cast<const float4 *>(ha.vhat + wbase + p));
+                        float vv[4] = {pv.x, pv.y, pv.z, pv.w}, vh[4] = {ph.x, ph.y, ph.z, ph.w};
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const float mm = (ha.beta1 * mv[t]) + (ha.omb1 * gv[t]);
-                        const float ein = ((selbits[it] >> t) & 1u) ? 0.0f : ev[t];   // e_t is zero on I_t
-                        mo[t] = mm;
-                        uv[t] = mm + (ha.rho * ein);
-                        gs[it][t] = (i == 0) ? gv[t] : (gs[it][t] + gv[t]);
+                        for (int t = 0; t < 4; ++t) {
+                            const float mm = (ha.beta1 * mv[t]) + (ha.omb1 * gv[t]);
+                            const float v2 = (ha.beta2 * vv[t]) + (ha.omb2 * (gv[t] * gv[t]));
+                            const float ein = ((selbits[it] >> t) & 1u) ? 0.0f : ev[t];   // e_t is zero on I_t
+                            mo[t] = mm;
+                            vv[t] = v2;
+                            if (v2 > vh[t]) vh[t] = v2;
+                            uv[t] = (mm / sqrtf(vh[t])) + (ha.rho * ein);
+                        }
+                        store_stream(reinterpret_cast<float4 *>(ha.v + wbase + p), make_float4(vv[0], vv[1], vv[2], vv[3]));
+                        store_stream(reinterpret_cast<float4 *>(ha.vhat + wbase + p), make_float4(vh[0], vh[1], vh[2], vh[3]));
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float mm = (ha.beta1 * mv[t]) + (ha.omb1 * gv[t]);
+                            const float ein = ((selbits[it] >> t) & 1u) ? 0.0f : ev[t];   // e_t is zero on I_t
+                            mo[t] = mm;
+                            uv[t] = mm + (ha.rho * ein);
+                            gs[it][t] = (i == 0) ? gv[t] : (gs[it][t] + gv[t]);
+                        }
                     }
                     store_stream(reinterpret_cast<float4 *>(ha.m + wbase + p), make_float4(mo[0], mo[1], mo[2], mo[3]));
                     store_stream(reinterpret_cast<float4 *>(ha.e + wbase + p), make_float4(uv[0], uv[1], uv[2], uv[3]));
@@ -420,6 +440,7 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
         }
         __syncthreads();
     }
+    if constexpr (PA) return;                                        // the second moments were per worker, above
     const float fn = (float)n;
 #pragma unroll
     for (int it = 0; it < kFusedIters; ++it) {
@@ -897,7 +918,8 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         hipError_t e = hipFuncSetAttribute((const void *)k_plan_sort, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_chain, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
 #define SAMS_CM(RR, IT)                                                                            \
     if (e == hipSuccess)                                                                           \
         e = hipFuncSetAttribute((const void *)k_bin_collect_median<RR, IT>,                        \
@@ -1008,7 +1030,7 @@ bool head_can_fuse(const sams_ctx *ctx)
 }
 
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
-                         float beta1, float beta2, float rho)
+                         float beta1, float beta2, float rho, bool pa)
 {
     Plan &pl = ctx->plan;
     const int64_t L = (int64_t)1 << pl.tile_log2;
@@ -1016,10 +1038,16 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
     HeadArgs ha = {g, m, e_u, v, vhat, ctx->bitmap, beta1, 1.0f - beta1, beta2, 1.0f - beta2, rho};
     {
         ProfScope ps(ctx, KID_HEAD_SCATTER);
-        hipLaunchKernelGGL(k_head_scatter, dim3((unsigned)(per * kNumXcd)), dim3(kFusedThreads), (size_t)(L * 4),
-                           ctx->stream, ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n,
-                           RowGroup{0, pl.stage_rows, pl.stage_rows, ctx->r}, ctx->d, pl.tile_log2, pl.ntile,
-                           pl.rowlen);
+        const dim3 grid((unsigned)(per * kNumXcd));
+        const RowGroup rg = {0, pl.stage_rows, pl.stage_rows, ctx->r};
+        if (pa)
+            hipLaunchKernelGGL(k_head_scatter<true>, grid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream, ha,
+                               pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
+                               pl.rowlen);
+        else
+            hipLaunchKernelGGL(k_head_scatter<false>, grid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream, ha,
+                               pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
+                               pl.rowlen);
     }
     SAMS_HIP(hipGetLastError());
     pl.staged_u = e_u;          // the staging now holds the sorted copy of this vector

@@ -51,6 +51,16 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
 }
 
 
+@pytest.fixture(params=[0, 1], ids=["separate-head", "fused-head"])
+def fused(request, sams):
+    """Default launch configuration with the head either on its own or fused with the first sketch pass."""
+    sams.sams_configure("fuse_head", request.param)
+    sams.sams_configure("sketch_path", 2 if request.param else 0)    # the fused head needs the binned path
+    yield request.param
+    sams.sams_configure("fuse_head", 0)
+    sams.sams_configure("sketch_path", 0)
+
+
 @pytest.fixture(params=list(PATHS))
 def path(request, sams):
     for key, val in PATHS[request.param].items():
@@ -314,7 +324,7 @@ def test_chained_steps_with_overselection_follow_the_oracle(sams, wl, d, P):
 
 
 @pytest.mark.parametrize("d,n,r,c,k", SHAPES)
-def test_amsgrad_ef_update_pa_bit_exact(sams, d, n, r, c, k):
+def test_amsgrad_ef_update_pa_bit_exact(sams, fused, d, n, r, c, k):
     rng = np.random.default_rng(d + 7)
     o = Oracle("f32")
     b1, b2, lr = 0.9, 0.999, 1e-3
@@ -335,13 +345,18 @@ def test_amsgrad_ef_update_pa_bit_exact(sams, d, n, r, c, k):
         o.head_pa(g2, m, e, vw, vhw, b1, b2, rho=1.25)
         for got, want in ((md, m), (ed, e), (vd, vw), (vhd, vhw), (xd, x)):
             assert np.array_equal(host(got), want)
+        if ctx.sketch_mode == 2:                      # a fused head has left the sorted copy of e_u behind: use it
+            S = torch.empty((n, r, c), device="cuda")
+            ctx.sketch_accumulate(ed, S)
+            hp = inputs.hash_params(r)
+            assert np.array_equal(host(S), np.stack([o.sketch(e[i], hp, c) for i in range(n)]))
         ctx.amsgrad_ef_update_pa(None, md, ed, vd, vhd, xd, dev(idx), dev(delta), k, b1, b2, lr)
         o.tail(e, x, idx, delta, lr)
         assert np.array_equal(host(ed), e) and np.array_equal(host(xd), x)
 
 
 @pytest.mark.parametrize("wl,d", [("C2", 300_000), ("P1", 400_000), ("P2b", 60_000)])
-def test_chained_parameter_averaging_steps_follow_the_oracle(sams, wl, d):
+def test_chained_parameter_averaging_steps_follow_the_oracle(sams, fused, wl, d):
     """Alg. 1 end to end: per-worker second moments, plain unsketch operator, unscaled second round."""
     w = inputs.WORKLOADS[wl].scaled(d) if d != inputs.WORKLOADS[wl].d else inputs.WORKLOADS[wl]
     gs = inputs.GradientStream(w, device="cuda")
