@@ -39,6 +39,7 @@ def kernel_algorithmic_bytes(name, d, n, r, c, k, pa=False):
         "k_bin_scatter": 4 * n * d,             # reads u once; the staging it writes is not algorithmic
         "k_bin_accumulate": n * rc4,            # writes every table cell once; the staging it reads is not
         "k_sketch_lds": 4 * n * d + n * rc4,
+        "k_head_sparse_v": k * (4 * n + 4 + 16),  # idx, g of every worker, v and vhat read and written
         "k_head_pa": 36 * n * d,                # g, m, e, v, vhat read; m, u, v, vhat written
         # the head's own traffic; the staging it also writes is not
         "k_head_scatter": 36 * n * d if pa else 20 * n * d + 12 * d,
@@ -103,7 +104,7 @@ def main():
                     help="P of the paper's second round: P*k candidates, then topk_refine (default 1: none)")
     ap.add_argument("--no-vram-precondition", action="store_true",
                     help="skip the allocate-and-free pass over the free device memory before the buffers are created")
-    ap.add_argument("--tune", default="fuse_head=1",
+    ap.add_argument("--tune", default="fuse_head=2",
                     help="library tunables (sams_configure), e.g. fuse_head=1,tile_log2=14,win_log2=15")
     args = ap.parse_args()
     if args.gpus != 1:

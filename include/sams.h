@@ -79,10 +79,13 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "run_pad"     16 or 32 (default 32): stream positions a (tile, window) run is padded to, so that the
  *                 staging writes cover whole 64- or 128-byte lines
  *   "scatter_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned scatter pass
- *   "fuse_head"   0 (default) or 1: with 1, amsgrad_ef_update or amsgrad_ef_update_pa (when it runs the head and the context uses
+ *   "fuse_head"   0 (default), 1 or 2: with 1 or 2, amsgrad_ef_update or amsgrad_ef_update_pa (when it runs the head and the context uses
  *                 the binned path) also writes the sorted copy of e_u that sketch_accumulate needs, and a
  *                 following sketch_accumulate called with that same e_u pointer skips its first pass.
  *                 The caller must then not write to e_u between the two calls (the algorithm never does).
+ *                 1: one workgroup per tile loops over the workers; 2: one workgroup per (tile, worker), the
+ *                 workers of a tile sharing the plan's metadata through one L2, and the (1 - beta2) h^2 term of
+ *                 v on I_{t-1} added by a small kernel of its own (same results bit for bit).
  *   "stage_rows"  0..16 (default 0 = all r rows): rows of the sketch staged at once on the binned path; the
  *                 staging buffer holds 4*n*stage_rows*(1.1 to 1.5)*d bytes and stage 1 runs row group after
  *                 row group (each group after the first re-reads u)

@@ -15,7 +15,7 @@ static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
     "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds", "k_bin_lookup",
-    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map", "k_head_pa"};
+    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map", "k_head_pa", "k_head_sparse_v"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -173,7 +173,7 @@ int sams_configure(const char *key, int value)
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.estimate_path = value;
     } else if (!strcmp(key, "fuse_head")) {
-        if (value < 0 || value > 1) return SAMS_EINVAL;
+        if (value < 0 || value > 2) return SAMS_EINVAL;
         g_tun.fuse_head = value;
     } else if (!strcmp(key, "fuse_median")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
@@ -319,7 +319,7 @@ int amsgrad_ef_update(sams_ctx *ctx, const float *g_next, float *m, float *e_u, 
     SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
     if (g_next) {
         if (head_can_fuse(ctx))
-            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio, false));
+            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio, false, idx, k_sel));
         else
             SAMS_TRY(enqueue_head(ctx, g_next, m, e_u, v, vhat, beta1, beta2, ef_ratio));
     }
@@ -339,7 +339,7 @@ int amsgrad_ef_update_pa(sams_ctx *ctx, const float *g_next, float *m, float *e_
     SAMS_TRY(enqueue_tail(ctx, e_u, x, idx, delta, k_sel, lr, g_next == nullptr));
     if (g_next) {
         if (head_can_fuse(ctx))
-            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio, true));
+            SAMS_TRY(enqueue_head_scatter(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio, true, idx, k_sel));
         else
             SAMS_TRY(enqueue_head_pa(ctx, g_next, m, e_u, v_workers, vhat_workers, beta1, beta2, ef_ratio));
     }

@@ -44,7 +44,7 @@ enum KernelId {
     KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
     KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
     KID_GATHER, KID_PLAN_BUILD, KID_BIN_SCATTER, KID_BIN_ACCUMULATE, KID_SKETCH_LDS, KID_BIN_LOOKUP,
-    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_HEAD_PA, KID_COUNT
+    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_HEAD_PA, KID_HEAD_SPARSE_V, KID_COUNT
 };
 const char *kernel_name(int kid);
 
@@ -85,7 +85,7 @@ struct Tunables {
     int sketch_path;   // 0 = choose from c and d, 1 = global atomics, 2 = ordered (binned) always, 3 = LDS atomics when c fits a window
     int scatter_threads;  // workgroup size of the scatter kernel
     int estimate_path;    // 0 = stage 3 through the plan when there is one, 1 = direct gathers from the table
-    int fuse_head;        // 1 = amsgrad_ef_update also stages u for the next sketch_accumulate
+    int fuse_head;        // 1, 2 = amsgrad_ef_update also stages u for the next sketch_accumulate (2: a workgroup per worker)
     int fuse_median;      // 1 = recovery keeps the row estimates in registers where the shape allows, 0 = through memory
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats
     int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
@@ -196,7 +196,8 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
 int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done);
 bool head_can_fuse(const sams_ctx *ctx);
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
-                         float beta1, float beta2, float rho, bool pa);   // pa: v, vhat are [n][d] (Alg. 1)
+                         float beta1, float beta2, float rho, bool pa,   // pa: v, vhat are [n][d] (Alg. 1)
+                         const int32_t *idx_prev, int64_t k_prev);       // I_{t-1}, as handed to the tail
 // sams_select.hip
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
 int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel);

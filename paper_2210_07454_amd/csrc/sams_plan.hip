@@ -462,6 +462,123 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
     }
 }
 
+// The same work with one workgroup per (tile, worker): the n workgroups of a tile sit on the same XCD in
+// consecutive slots and walk the tile's plan metadata at about the same time, so that it comes from HBM once
+// and from that XCD's L2 for the others, instead of being re-read through the fabric once per worker.
+// The second moments of Alg. 2 need the mean gradient over the workers, but only on I_{t-1}: worker 0's
+// workgroup decays v everywhere (the update with h = 0, which is what every other coordinate gets) and
+// k_head_sparse_v then adds the (1 - beta2) h^2 term on I_{t-1}.  Rounding is that of the one-step formula:
+// v' = beta2 v (+ 0), then v = v' + (1 - beta2) h^2; vhat = max(max(vhat, v'), v) = max(vhat, v) since v >= v'.
+// (Fetching the other workers' g for those coordinates inside worker 0's workgroup instead was tried: its
+// divergent, dependent gathers made the kernel 1.5x slower.)
+template <bool PA>
+__global__ void __launch_bounds__(kFusedThreads)
+k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
+                 const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
+                 int tile_log2, int64_t ntile, int64_t rowlen)
+{
+    extern __shared__ float tilebuf[];
+    const int L = 1 << tile_log2;
+    const int64_t per = (ntile + kNumXcd - 1) / kNumXcd;
+    const int64_t slot = blockIdx.x / kNumXcd;
+    const int32_t i = (int32_t)(slot % n);
+    const int64_t tile = (int64_t)(blockIdx.x % kNumXcd) * per + slot / n;
+    if (slot / n >= per || tile >= ntile) return;
+    const int64_t l0 = tile << tile_log2;
+    const int64_t wbase = (int64_t)i * d + l0;
+#pragma unroll
+    for (int it = 0; it < kFusedIters; ++it) {
+        const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+        if (p < L) {
+            float uv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (l0 + p < d) {
+                const uint32_t selbits = (ha.bitmap[(l0 + p) >> 5] >> ((l0 + p) & 31)) & 0xFu;
+                const float4 a = load_stream(reinterpret_cast<const float4 *>(ha.g + wbase + p));
+                const float4 b = load_stream(reinterpret_cast<const float4 *>(ha.m + wbase + p));
+                const float4 cc = load_stream(reinterpret_cast<const float4 *>(ha.e + wbase + p));
+                const float gv[4] = {a.x, a.y, a.z, a.w}, mv[4] = {b.x, b.y, b.z, b.w}, ev[4] = {cc.x, cc.y, cc.z, cc.w};
+                float mo[4];
+                if constexpr (PA) {
+                    const float4 pv = load_stream(reinterpret_cast<const float4 *>(ha.v + wbase + p));
+                    const float4 ph = load_stream(reinterpret_cast<const float4 *>(ha.vhat + wbase + p));
+                    float vv[4] = {pv.x, pv.y, pv.z, pv.w}, vh[4] = {ph.x, ph.y, ph.z, ph.w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float mm = (ha.beta1 * mv[t]) + (ha.omb1 * gv[t]);
+                        const float v2 = (ha.beta2 * vv[t]) + (ha.omb2 * (gv[t] * gv[t]));
+                        const float ein = ((selbits >> t) & 1u) ? 0.0f : ev[t];          // e_t is zero on I_t
+                        mo[t] = mm;
+                        vv[t] = v2;
+                        if (v2 > vh[t]) vh[t] = v2;
+                        uv[t] = (mm / sqrtf(vh[t])) + (ha.rho * ein);
+                    }
+                    store_stream(reinterpret_cast<float4 *>(ha.v + wbase + p), make_float4(vv[0], vv[1], vv[2], vv[3]));
+                    store_stream(reinterpret_cast<float4 *>(ha.vhat + wbase + p), make_float4(vh[0], vh[1], vh[2], vh[3]));
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float mm = (ha.beta1 * mv[t]) + (ha.omb1 * gv[t]);
+                        const float ein = ((selbits >> t) & 1u) ? 0.0f : ev[t];          // e_t is zero on I_t
+                        mo[t] = mm;
+                        uv[t] = mm + (ha.rho * ein);
+                    }
+                    if (i == 0) {                                    // the decay of v, once per coordinate
+                        const float4 vin = *reinterpret_cast<const float4 *>(ha.v + l0 + p);
+                        const float4 hin = *reinterpret_cast<const float4 *>(ha.vhat + l0 + p);
+                        float vv[4] = {vin.x, vin.y, vin.z, vin.w}, vh[4] = {hin.x, hin.y, hin.z, hin.w};
+                        bool moved = false;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            vv[t] = (ha.beta2 * vv[t]);              // + (1 - beta2) * 0^2, exactly
+                            if (vv[t] > vh[t]) { vh[t] = vv[t]; moved = true; }
+                        }
+                        *reinterpret_cast<float4 *>(ha.v + l0 + p) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+                        if (moved) *reinterpret_cast<float4 *>(ha.vhat + l0 + p) = make_float4(vh[0], vh[1], vh[2], vh[3]);
+                    }
+                }
+                store_stream(reinterpret_cast<float4 *>(ha.m + wbase + p), make_float4(mo[0], mo[1], mo[2], mo[3]));
+                store_stream(reinterpret_cast<float4 *>(ha.e + wbase + p), make_float4(uv[0], uv[1], uv[2], uv[3]));
+            }
+            *reinterpret_cast<float4 *>(tilebuf + p) = make_float4(uv[0], uv[1], uv[2], uv[3]);
+        }
+    }
+    __syncthreads();
+    for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
+        const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
+        const uint16_t *sj = srcp + (int64_t)j * rowlen;
+        const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+        float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
+        for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
+            const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
+            const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+            const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu, s3 = packed.y >> 16;
+            float4 v;
+            v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
+            v.y = (s1 == kSrcPad) ? 0.f : tilebuf[s1 & 0x7fffu]; v.y = (s1 & 0x8000u) ? -v.y : v.y;
+            v.z = (s2 == kSrcPad) ? 0.f : tilebuf[s2 & 0x7fffu]; v.z = (s2 & 0x8000u) ? -v.z : v.z;
+            v.w = (s3 == kSrcPad) ? 0.f : tilebuf[s3 & 0x7fffu]; v.w = (s3 & 0x8000u) ? -v.w : v.w;
+            store_stream(reinterpret_cast<float4 *>(oj + at), v);
+        }
+    }
+}
+
+// v and vhat on I_{t-1} after k_head_scatter_w has decayed them: h = mean over the workers of g (summed in
+// worker order, as everywhere), v += (1 - beta2) h^2, vhat = max(vhat, v)   (Alg. 2, master lines)
+__global__ void __launch_bounds__(256)
+k_head_sparse_v(const float *__restrict__ g, const int32_t *__restrict__ idx, int64_t k_sel, int32_t n, int64_t d,
+                float omb2, float *__restrict__ v, float *__restrict__ vhat)
+{
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= k_sel) return;
+    const int64_t l = idx[q];
+    float gs = g[l];
+    for (int32_t i = 1; i < n; ++i) gs = (gs + g[(int64_t)i * d + l]);
+    const float h = (gs / (float)n);
+    const float vv = (v[l] + (omb2 * (h * h)));
+    v[l] = vv;
+    if (vv > vhat[l]) vhat[l] = vv;
+}
+
 // ------------------------------------------------------------------------------------------
 // pass 2: per (worker, row, bin), add the bin's stream into an LDS window, chunk by chunk
 // ------------------------------------------------------------------------------------------
@@ -920,6 +1037,8 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter_w<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_scatter_w<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
 #define SAMS_CM(RR, IT)                                                                            \
     if (e == hipSuccess)                                                                           \
         e = hipFuncSetAttribute((const void *)k_bin_collect_median<RR, IT>,                        \
@@ -1030,7 +1149,7 @@ bool head_can_fuse(const sams_ctx *ctx)
 }
 
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
-                         float beta1, float beta2, float rho, bool pa)
+                         float beta1, float beta2, float rho, bool pa, const int32_t *idx_prev, int64_t k_prev)
 {
     Plan &pl = ctx->plan;
     const int64_t L = (int64_t)1 << pl.tile_log2;
@@ -1040,7 +1159,17 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
         ProfScope ps(ctx, KID_HEAD_SCATTER);
         const dim3 grid((unsigned)(per * kNumXcd));
         const RowGroup rg = {0, pl.stage_rows, pl.stage_rows, ctx->r};
-        if (pa)
+        if (g_tun.fuse_head == 2) {                                  // one workgroup per (tile, worker)
+            const dim3 wgrid((unsigned)(per * kNumXcd * ctx->n));
+            if (pa)
+                hipLaunchKernelGGL(k_head_scatter_w<true>, wgrid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream,
+                                   ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2,
+                                   pl.ntile, pl.rowlen);
+            else
+                hipLaunchKernelGGL(k_head_scatter_w<false>, wgrid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream,
+                                   ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2,
+                                   pl.ntile, pl.rowlen);
+        } else if (pa)
             hipLaunchKernelGGL(k_head_scatter<true>, grid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream, ha,
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
                                pl.rowlen);
@@ -1049,6 +1178,9 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
                                pl.rowlen);
     }
+    if (g_tun.fuse_head == 2 && !pa && k_prev > 0)
+        SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v, (unsigned)((k_prev + 255) / 256), 256, g, idx_prev, k_prev,
+                    ctx->n, ctx->d, 1.0f - beta2, v, vhat);
     SAMS_HIP(hipGetLastError());
     pl.staged_u = e_u;          // the staging now holds the sorted copy of this vector
     return SAMS_OK;

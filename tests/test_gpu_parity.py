@@ -42,6 +42,8 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
                        scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=0, fuse_median=1),
     "fused-head-small-tiles": dict(tile_log2=9, win_log2=7, chunk_log2=9, acc_threads=256, run_pad=16,
                                    scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=0, fuse_median=1),
+    "fused-head-per-worker": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=32,
+                                  scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0, fuse_median=1),
     "row-groups": dict(tile_log2=11, win_log2=9, chunk_log2=10, acc_threads=512, run_pad=32,
                        scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=2, fuse_median=1),
     "one-row-at-a-time": dict(tile_log2=12, win_log2=10, chunk_log2=10, acc_threads=1024, run_pad=16,
@@ -51,7 +53,7 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
 }
 
 
-@pytest.fixture(params=[0, 1], ids=["separate-head", "fused-head"])
+@pytest.fixture(params=[0, 1, 2], ids=["separate-head", "fused-head", "fused-head-per-worker"])
 def fused(request, sams):
     """Default launch configuration with the head either on its own or fused with the first sketch pass."""
     sams.sams_configure("fuse_head", request.param)
