@@ -1,5 +1,5 @@
 """Parity at the full sizes of the workloads, in the launch configuration bench.py times (default tunables
-plus the fused head).  Two iterations are run on the GPU; the second one is checked stage by stage:
+plus the fused head with a workgroup per (tile, worker)).  Two iterations are run on the GPU; the second one is checked stage by stage:
 the dense update on every element, the sketch tables of whole workers, every estimate, the gathered
 values -- bit for bit against the oracle fed with the GPU's own inputs of that stage.  The index set is
 compared with the oracle's full sort where that takes seconds, and otherwise through the properties that
@@ -42,7 +42,7 @@ def test_full_size_second_iteration_matches_oracle(wl, full_sort, sketch_workers
     from paper_2210_07454_amd import sams
     w = inputs.WORKLOADS[wl]
     d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
-    sams.sams_configure("fuse_head", 1)
+    sams.sams_configure("fuse_head", 2)
     try:
         gs = inputs.GradientStream(w, device="cuda")
         hp = inputs.hash_params(r, seed=w.seed)
@@ -121,7 +121,7 @@ def test_stress_size_second_iteration_sampled(capfd):
     free, total = torch.cuda.mem_get_info()
     if total < 250 * 2**30:
         pytest.skip("needs a 288 GB device")
-    tun = dict(fuse_head=1, stage_rows=2, run_pad=16)
+    tun = dict(fuse_head=2, stage_rows=2, run_pad=16)
     for key, val in tun.items():
         sams.sams_configure(key, val)
     try:
