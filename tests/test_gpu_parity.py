@@ -528,6 +528,15 @@ def test_invalid_arguments_are_rejected_without_launching(sams):
         assert ctx.scratch_bytes >= 4 * 1000
 
 
+def test_precondition_device_memory_leaves_nothing_behind(sams):
+    free0, _ = torch.cuda.mem_get_info()
+    held = sams.sams_precondition_device_memory(0.05)              # a twentieth of the free memory, in 1 GiB blocks
+    free1, _ = torch.cuda.mem_get_info()
+    assert held >= 1 and abs(free1 - free0) < (64 << 20)
+    with pytest.raises(sams.SamsError):
+        sams.sams_precondition_device_memory(0.0)
+
+
 def test_step_on_a_side_stream_and_as_a_replayed_hip_graph(sams):
     """No entry point synchronises the host or allocates, so a whole step can be captured once into a HIP graph on
     the context's stream and replayed.  Every replay (with eager work and synchronisations in between) must give
