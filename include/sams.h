@@ -76,8 +76,8 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "acc_threads" 0, 256, 512 or 1024 (default 0 = 1024 for 2^15 windows, else 512): workgroup size of the binned accumulation; must not
  *                 exceed 2^chunk_log2, and a window plus two chunks of 8 bytes must fit in 160 KiB of LDS
  *                 (otherwise sams_create returns SAMS_EINVAL)
- *   "run_pad"     16 or 32 (default 32): stream positions a (tile, window) run is padded to, so that the
- *                 staging writes cover whole 64- or 128-byte lines
+ *   "run_pad"     16 (default) or 32: stream positions a (tile, window) run is padded to, so that the
+ *                 staging writes cover whole 64- or 128-byte pieces
  *   "scatter_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned scatter pass
  *   "fuse_head"   0 (default), 1 or 2: with 1 or 2, amsgrad_ef_update or amsgrad_ef_update_pa (when it runs the head and the context uses
  *                 the binned path) also writes the sorted copy of e_u that sketch_accumulate needs, and a

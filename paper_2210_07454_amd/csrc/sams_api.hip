@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 32};
+Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",

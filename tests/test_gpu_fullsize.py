@@ -200,5 +200,5 @@ def test_stress_size_second_iteration_sampled(capfd):
             assert not host(b.e_u[:, il].contiguous()).any()
             say("gather and tail checked")
     finally:
-        for key, val in dict(fuse_head=0, stage_rows=0, run_pad=32).items():
+        for key, val in dict(fuse_head=0, stage_rows=0, run_pad=16).items():
             sams.sams_configure(key, val)
