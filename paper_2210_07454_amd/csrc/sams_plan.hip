@@ -290,8 +290,10 @@ k_plan_chain(int chunk_log2, int64_t rowlen, uint32_t *__restrict__ meta)
 // ------------------------------------------------------------------------------------------
 // pass 1: per tile, every worker's values to their positions in the row streams
 // ------------------------------------------------------------------------------------------
-// Workgroup ids are dealt round-robin to the 8 XCDs; consecutive tiles are given to the same XCD so that
-// neighbouring runs of a bin are written through one L2.  A thread owns 4 consecutive slots (always inside
+// One workgroup per (tile, worker).  Workgroup ids are dealt round-robin to the 8 XCDs; consecutive tiles are
+// given to the same XCD so that neighbouring runs of a bin are written through one L2, and the n workers of
+// a tile sit there in consecutive slots so that the tile's plan metadata crosses the fabric once and comes
+// from that L2 for the other workers.  A thread owns 4 consecutive slots (always inside
 // one group of 16, hence one run): one 8-byte load of their sources, one 4-byte load of the group's
 // stream position, 4 LDS reads and one 16-byte store -- nothing depends on another global load.
 __global__ void __launch_bounds__(1024)
@@ -302,11 +304,13 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
     extern __shared__ float tilebuf[];
     const int L = 1 << tile_log2;
     const int64_t per = (ntile + kNumXcd - 1) / kNumXcd;
-    const int64_t tile = (int64_t)(blockIdx.x % kNumXcd) * per + blockIdx.x / kNumXcd;
+    const int64_t slot = blockIdx.x / kNumXcd;
+    const int32_t i = (int32_t)(slot % n);
+    const int64_t tile = (int64_t)(blockIdx.x % kNumXcd) * per + slot / n;
     if (tile >= ntile) return;
     const int64_t l0 = tile << tile_log2;
     const bool vec = (d & 3) == 0;
-    for (int32_t i = 0; i < n; ++i) {
+    {
         const float *ui = u + (int64_t)i * d;
         if (vec) {
             for (int p = threadIdx.x * 4; p < L; p += blockDim.x * 4) {
@@ -336,7 +340,6 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
                 store_stream(reinterpret_cast<float4 *>(oj + at), v);
             }
         }
-        __syncthreads();
     }
 }
 
@@ -1211,7 +1214,7 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
         const RowGroup rg = {j0, (ctx->r - j0) < pl.stage_rows ? (ctx->r - j0) : pl.stage_rows, pl.stage_rows, ctx->r};
         if (j0 > 0 || pl.staged_u != u) {                            // not staged by a fused head: pass 1 now
             ProfScope ps(ctx, KID_BIN_SCATTER);
-            hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd)), dim3((unsigned)g_tun.scatter_threads),
+            hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd * ctx->n)), dim3((unsigned)g_tun.scatter_threads),
                                (size_t)(L * 4), ctx->stream, u, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg,
                                ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);
         }
