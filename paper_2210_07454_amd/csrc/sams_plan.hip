@@ -33,6 +33,7 @@ namespace sams {
 constexpr int kPlanThreads = 1024;
 constexpr int kScatterThreads = 256;
 constexpr int kNumXcd = 8;
+constexpr int kScatterBatch = 4;             // groups of 4 slots whose metadata a scatter thread loads ahead
 constexpr int kAccDepth = 8;                // chunks in flight per workgroup of the accumulate kernel
 constexpr int kFusedThreads = 1024;          // kernels whose threads own the same 4-coordinate groups throughout
 constexpr int kFusedIters = 4;              // tiles of at most 2^14 coordinates = 4 float4 per thread
@@ -327,17 +328,31 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
             const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
             float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
-            for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
-                const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-                const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
-                const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
-                               s3 = packed.y >> 16;
-                float4 v;
-                v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
-                v.y = (s1 == kSrcPad) ? 0.f : tilebuf[s1 & 0x7fffu]; v.y = (s1 & 0x8000u) ? -v.y : v.y;
-                v.z = (s2 == kSrcPad) ? 0.f : tilebuf[s2 & 0x7fffu]; v.z = (s2 & 0x8000u) ? -v.z : v.z;
-                v.w = (s3 == kSrcPad) ? 0.f : tilebuf[s3 & 0x7fffu]; v.w = (s3 & 0x8000u) ? -v.w : v.w;
-                store_stream(reinterpret_cast<float4 *>(oj + at), v);
+            // four groups of 4 slots per thread and batch: their sources and positions are loaded unconditionally
+            // (clamped addresses; o1 - o0 is a multiple of 16, at least 16) before the first is used
+            for (uint32_t ob = o0 + threadIdx.x * 4; ob < o1; ob += blockDim.x * 4 * kScatterBatch) {
+                uint2 packed4[kScatterBatch];
+                uint32_t at4[kScatterBatch];
+#pragma unroll
+                for (int uu = 0; uu < kScatterBatch; ++uu) {
+                    const uint32_t o = ob + (uint32_t)uu * blockDim.x * 4, oc = o < o1 ? o : o1 - 4;
+                    packed4[uu] = *reinterpret_cast<const uint2 *>(sj + oc);
+                    at4[uu] = dj[oc / kRunPad] + (oc & (kRunPad - 1));
+                }
+#pragma unroll
+                for (int uu = 0; uu < kScatterBatch; ++uu) {
+                    if (ob + (uint32_t)uu * blockDim.x * 4 < o1) {
+                        const uint2 packed = packed4[uu];
+                        const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
+                                       s3 = packed.y >> 16;
+                        float4 v;
+                        v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
+                        v.y = (s1 == kSrcPad) ? 0.f : tilebuf[s1 & 0x7fffu]; v.y = (s1 & 0x8000u) ? -v.y : v.y;
+                        v.z = (s2 == kSrcPad) ? 0.f : tilebuf[s2 & 0x7fffu]; v.z = (s2 & 0x8000u) ? -v.z : v.z;
+                        v.w = (s3 == kSrcPad) ? 0.f : tilebuf[s3 & 0x7fffu]; v.w = (s3 & 0x8000u) ? -v.w : v.w;
+                        store_stream(reinterpret_cast<float4 *>(oj + at4[uu]), v);
+                    }
+                }
             }
         }
     }
