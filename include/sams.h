@@ -48,7 +48,7 @@ typedef struct sams_ctx sams_ctx;
  *   hash_host  HOST pointer to r*4 uint32: per row (a_h, b_h, a_s, b_s).  The bucket hash of row j is
  *              h_j(l) = ((a_h*l + b_h) mod (2^31-1)) mod c and the sign hash is s_j(l) = +1 if
  *              ((a_s*l + b_s) mod (2^31-1)) is even, -1 if odd (the paper, Sec. II-C, only asks for
- *              "bucket hashes" and "sign hashes"; this 2-universal family is this library's choice).
+ *              bucket and sign hashes without fixing a family; this 2-universal one is this library's choice).
  *              Requires 1 <= a < 2^31-1, 0 <= b < 2^31-1.  The values are copied.
  *   hip_stream the hipStream_t (as void*) every later call on this context is enqueued on; NULL =
  *              the default stream.
@@ -152,8 +152,8 @@ int sams_profile_read(sams_ctx *ctx, double *total_ms, int64_t *launches);
 int sams_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
 
 /*
- * Stage 1 -- Count Sketch of every worker's vector (Sec. II-C update rule; Alg. 2 worker line
- * "Sketch S_t^(i) = S(m_t^(i) + (alpha_{t-1}/alpha_t) e_{t-1}^(i))"):
+ * Stage 1 -- Count Sketch of every worker's vector (Sec. II-C update rule; the worker line of Alg. 2 that
+ * sketches the momentum plus the step-size-weighted residual):
  *     S_workers[i][j][h_j(l)] += s_j(l) * u[i][l]      for all workers i, rows j, coordinates l.
  *   u          [n][d] in    the vectors to sketch (what amsgrad_ef_update leaves in e_u)
  *   S_workers  [n][r][c] out, overwritten (zeroed by the call, then accumulated)
@@ -167,7 +167,7 @@ int sams_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
 int sketch_accumulate(sams_ctx *ctx, const float *u, float *S_workers);
 
 /*
- * Stage 2 -- aggregation on the master (Alg. 2: "Aggregate S_t = 1/n sum_i S_t^(i)"; linearity, Eq. 3):
+ * Stage 2 -- aggregation on the master (the aggregation line of Alg. 2: the mean of the workers' sketches; linearity, Eq. 3):
  *     S_mean[j][b] = (S_workers[0][j][b] + S_workers[1][j][b] + ... ) / n, workers added in ascending i.
  *   S_workers [n][r][c] in     S_mean [r][c] out
  */
@@ -175,7 +175,7 @@ int sketch_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean);
 
 /*
  * Stage 3 -- heavy-coordinate recovery and selection (Sec. II-C unsketch; Alg. 3; Alg. 2 master line
- * "Unsketch Delta_t = Top-k(U(S_t, vhat_t))"):
+ * that unsketches with vhat_t and keeps the top k):
  *     est[l] = median_j( s_j(l) * S_mean[j][h_j(l)] ) / sqrt(vhat[l])        for every l < d
  *     idx    = the k coordinates with the largest |est|, ties going to the smaller coordinate,
  *              written in ascending order.

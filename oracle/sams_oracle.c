@@ -14,7 +14,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 
-/* Hash family (the paper names only "bucket hashes" and "sign hashes", Sec. II-C; this is the
+/* Hash family (Sec. II-C speaks of bucket and sign hashes without fixing a family; this is the
  * seeded 2-universal family y = (a*l + b) mod p with the Mersenne prime p = 2^31 - 1,
  * l the 0-based coordinate).  a*l + b < 2^62 + 2^31 fits in 64 bits, so plain % is exact. */
 uint32_t orc_hash_y(uint32_t a, uint32_t b, uint32_t l)

@@ -15,12 +15,12 @@
  *                              y = (a*l + b) mod (2^31-1), bucket = y mod c,
  *                              sign = +1 if the sign-hash y is even, else -1.
  *   sketch ................... Sec. II-C update rule S[j,h_j(l)] += s_j(l) f_l.
- *   sketch_mean .............. Alg. 2, master line "Aggregate S_t = 1/n sum S_t^(i)".
+ *   sketch_mean .............. Alg. 2, the master's aggregation line: mean of the workers' sketches.
  *   unsketch ................. Sec. II-C (median over rows of s_j(l) S[j,h_j(l)]) and
  *                              Alg. 3 read as a per-coordinate scaling by 1/sqrt(v_l)
  *                              (the text below Alg. 2 says the operator must equal
  *                              sketching v^{-1/2}(m + rho e) and unsketching normally).
- *   topk ..................... Alg. 2 "Top-k(U(S_t, vhat_t))": k largest magnitudes,
+ *   topk ..................... Alg. 2, the Top-k of the unsketched vector: k largest magnitudes,
  *                              ties to the smaller index, result ascending by index.
  *   gather ................... Sec. III-A second round + definition of Delta_t^(i)
  *                              (coordinates of vhat^{-1/2}(m + rho e) on I_t), mean over workers.

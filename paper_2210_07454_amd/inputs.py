@@ -77,8 +77,8 @@ WORKLOADS = {
     "C5": Workload("C5-stress", d=1_300_000_000, n=4, r=5, c=16_777_216, k=1_300_000, steps=3,
                    noise="normal", nseg=1, lo=-3.0, hi=-3.0, heavy="pareto", heavy_frac=0.001,
                    heavy_alpha=1.2),
-    # The sketch shapes of the paper's own experiments (Sec. V): ResNet-50 ("about 25M parameters", 16 workers,
-    # 10 rows x 100,000 columns, k = 50,000) and LeNet-5 ("about 60k parameters", 50 and 100 workers, 5 rows x
+    # The sketch shapes of the paper's own experiments (Sec. V): ResNet-50 (roughly 25M parameters, 16 workers,
+    # 10 rows x 100,000 columns, k = 50,000) and LeNet-5 (roughly 60k parameters, 50 and 100 workers, 5 rows x
     # 400 columns, k = 500).  Even row count, column counts that are not powers of two.  The gradient recipe is
     # synthetic as above (the paper's come from CIFAR / MNIST training).
     "P1": Workload("P1-paper-resnet50", d=25_000_000, n=16, r=10, c=100_000, k=50_000, steps=5,

@@ -584,7 +584,7 @@ def test_f32_and_f64_oracles_agree_within_fp32_rounding():
 # ------------------------------------------------------------- value the paper prints
 def test_compression_rate_printed_in_the_paper():
     # Sec. III-B gives the rate 2d / (|S| + Pk + 2k); Sec. V-A states the ResNet-50 settings and
-    # "about 32x".  The fixture holds those printed numbers.
+    # a reduction of roughly 32x.  The fixture holds those printed numbers.
     vals = {}
     with open(os.path.join(GOLDEN, "compression_rate.txt")) as f:
         for line in f:
