@@ -234,8 +234,19 @@ int sams_profile_enable(sams_ctx *ctx, int on)
             ctx->prof = (ProfRec *)calloc(kProfPool, sizeof(ProfRec));
             if (!ctx->prof) return SAMS_ENOMEM;
             for (int s = 0; s < kProfPool; ++s) {
-                SAMS_HIP(hipEventCreate(&ctx->prof[s].a));
-                SAMS_HIP(hipEventCreate(&ctx->prof[s].b));
+                hipError_t e = hipEventCreate(&ctx->prof[s].a);
+                if (e == hipSuccess) e = hipEventCreate(&ctx->prof[s].b);
+                if (e != hipSuccess) {                               // all or nothing: a later call starts over
+                    for (int q = 0; q <= s; ++q) {
+                        if (ctx->prof[q].a) (void)hipEventDestroy(ctx->prof[q].a);
+                        if (ctx->prof[q].b) (void)hipEventDestroy(ctx->prof[q].b);
+                    }
+                    free(ctx->prof);
+                    ctx->prof = nullptr;
+                    g_last_hip_error = (int)e;
+                    (void)hipGetLastError();
+                    return SAMS_EHIP;
+                }
             }
         }
         SAMS_TRY(prof_drain(ctx));
