@@ -89,6 +89,10 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "stage_rows"  0..16 (default 0 = all r rows): rows of the sketch staged at once on the binned path; the
  *                 staging buffer holds 4*n*stage_rows*(1.1 to 1.5)*d bytes and stage 1 runs row group after
  *                 row group (each group after the first re-reads u)
+ *   "stage_interleave" 1 (default) or 0: layout of the staging buffer.  1: the n workers' copies of the same 32 stream
+ *                 positions lie next to each other (one 128-byte line each), so that the workgroups of the workers,
+ *                 which run side by side, write and read one region per (row, window) instead of n distant ones;
+ *                 0: one contiguous copy per (worker, row).  Same results either way.
  *   "fuse_median" 1 (default) or 0: with 1 the plan-driven recovery keeps the row estimates in registers
  *                 (needs r <= 6 with tiles of 2^14, r <= 12 with 2^13, any r with 2^12 or less); with 0
  *                 they go through a [r][d] scratch array

@@ -61,10 +61,24 @@ __device__ __forceinline__ float4 load_stream(const float4 *p)
 }
 
 // Rows [j0, j0 + rj) of the r rows are handled by one launch; their staging is stg[n][sr][rowlen] with
-// row j at slot j - j0 (sr = rows the staging buffer was sized for, r in total).
+// row j at slot j - j0 (sr = rows the staging buffer was sized for, r in total).  With ilv set the layout is
+// stg[sr][rowlen / 32][n][32] instead: the workers' copies of the same 32 stream positions (one 128-byte line
+// each) lie next to each other, so that the workgroups of the n workers, which run side by side in both passes,
+// write and read one contiguous region per (row, bin) instead of n regions rowlen apart.
 struct RowGroup {
-    int32_t j0, rj, sr, r;
+    int32_t j0, rj, sr, r, ilv;
 };
+constexpr int kIlvLog2 = 5;
+
+// start of worker i's copy of staged row jj, and the offset of stream position p from there
+__device__ __forceinline__ int64_t stage_row(const RowGroup &rg, int32_t n, int64_t rowlen, int32_t i, int32_t jj)
+{
+    return rg.ilv ? (int64_t)jj * n * rowlen + ((int64_t)i << kIlvLog2) : ((int64_t)i * rg.sr + jj) * rowlen;
+}
+__device__ __forceinline__ int64_t stage_pos(const RowGroup &rg, int32_t n, uint32_t p)
+{
+    return rg.ilv ? ((int64_t)(p >> kIlvLog2) * n << kIlvLog2) + (p & ((1u << kIlvLog2) - 1u)) : (int64_t)p;
+}
 
 __host__ __device__ __forceinline__ int pad_run(int len, int pad) { return (len + pad - 1) & ~(pad - 1); }
 
@@ -327,17 +341,17 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
             const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
             const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
-            float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
+            float *oj = stg + stage_row(rg, n, rowlen, i, j - rg.j0);
             // four groups of 4 slots per thread and batch: their sources and positions are loaded unconditionally
             // (clamped addresses; o1 - o0 is a multiple of 16, at least 16) before the first is used
             for (uint32_t ob = o0 + threadIdx.x * 4; ob < o1; ob += blockDim.x * 4 * kScatterBatch) {
                 uint2 packed4[kScatterBatch];
-                uint32_t at4[kScatterBatch];
+                int64_t at4[kScatterBatch];
 #pragma unroll
                 for (int uu = 0; uu < kScatterBatch; ++uu) {
                     const uint32_t o = ob + (uint32_t)uu * blockDim.x * 4, oc = o < o1 ? o : o1 - 4;
                     packed4[uu] = *reinterpret_cast<const uint2 *>(sj + oc);
-                    at4[uu] = dj[oc / kRunPad] + (oc & (kRunPad - 1));
+                    at4[uu] = stage_pos(rg, n, dj[oc / kRunPad]) + (oc & (kRunPad - 1));
                 }
 #pragma unroll
                 for (int uu = 0; uu < kScatterBatch; ++uu) {
@@ -442,10 +456,10 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
             const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
             const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
-            float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
+            float *oj = stg + stage_row(rg, n, rowlen, i, j - rg.j0);
             for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
                 const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-                const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+                const int64_t at = stage_pos(rg, n, dj[o / kRunPad]) + (o & (kRunPad - 1));
                 const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
                                s3 = packed.y >> 16;
                 float4 v;
@@ -565,10 +579,10 @@ k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t 
         const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
         const uint16_t *sj = srcp + (int64_t)j * rowlen;
         const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
-        float *oj = stg + ((int64_t)i * rg.sr + (j - rg.j0)) * rowlen;
+        float *oj = stg + stage_row(rg, n, rowlen, i, j - rg.j0);
         for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
             const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-            const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+            const int64_t at = stage_pos(rg, n, dj[o / kRunPad]) + (o & (kRunPad - 1));
             const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu, s3 = packed.y >> 16;
             float4 v;
             v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
@@ -622,7 +636,11 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     const int64_t bin = group % nbins;
     for (int t = threadIdx.x; t < W; t += THREADS) win[t] = 0.f;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
-    const float *v = stg + ((int64_t)i * rg.sr + jj) * rowlen + b0;
+    // position b0 + x of the bin (x = chunk start + z * THREADS, a multiple of 32, plus the thread's index) is at
+    // v[x * vmul + voff]
+    const float *v = stg + stage_row(rg, n, rowlen, i, jj) + stage_pos(rg, n, (uint32_t)b0);
+    const int64_t vmul = rg.ilv ? n : 1;
+    const int64_t voff = stage_pos(rg, n, threadIdx.x);
     const uint32_t *m = meta + (int64_t)j * rowlen + b0;
     const int64_t nchunk = (b1 - b0) / CH;
     const uint32_t wmask = (uint32_t)W - 1u;
@@ -641,7 +659,7 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
             const int64_t qs = s < last ? s : last;
 #pragma unroll
             for (int z = 0; z < UNROLL; ++z) {
-                rv[s][z] = __builtin_nontemporal_load(v + qs * CH + z * THREADS + threadIdx.x);
+                rv[s][z] = __builtin_nontemporal_load(v + (qs * CH + z * THREADS) * vmul + voff);
                 rm[s][z] = m[qs * CH + z * THREADS + threadIdx.x];
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -675,7 +693,7 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
                 const int64_t qn = (q + kAccDepth) < last ? (q + kAccDepth) : last;
 #pragma unroll
                 for (int z = 0; z < UNROLL; ++z) {
-                    rv[s][z] = __builtin_nontemporal_load(v + qn * CH + z * THREADS + threadIdx.x);
+                    rv[s][z] = __builtin_nontemporal_load(v + (qn * CH + z * THREADS) * vmul + voff);
                     rm[s][z] = m[qn * CH + z * THREADS + threadIdx.x];
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -1013,6 +1031,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.chunk_log2 = tun.chunk_log2 ? tun.chunk_log2 : (pl.win_log2 >= 15 ? 11 : 10);
     pl.acc_threads = tun.acc_threads ? tun.acc_threads : (pl.win_log2 >= 15 ? 1024 : 512);
     pl.run_pad = tun.run_pad;
+    pl.stage_ilv = tun.stage_interleave ? 1 : 0;
     pl.stage_rows = (tun.stage_rows <= 0 || tun.stage_rows > ctx->r) ? ctx->r : tun.stage_rows;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
@@ -1067,7 +1086,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_bin_collect, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);   // + 1 KiB static
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
-        rc = dispatch_acc(ctx, nullptr, RowGroup{0, 0, 0, 0}, true);
+        rc = dispatch_acc(ctx, nullptr, RowGroup{0, 0, 0, 0, 0}, true);
         if (rc != SAMS_OK) break;
         {
             ProfScope ps(ctx, KID_PLAN_BUILD);
@@ -1176,7 +1195,7 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
     {
         ProfScope ps(ctx, KID_HEAD_SCATTER);
         const dim3 grid((unsigned)(per * kNumXcd));
-        const RowGroup rg = {0, pl.stage_rows, pl.stage_rows, ctx->r};
+        const RowGroup rg = {0, pl.stage_rows, pl.stage_rows, ctx->r, pl.stage_ilv};
         if (g_tun.fuse_head == 2) {                                  // one workgroup per (tile, worker)
             const dim3 wgrid((unsigned)(per * kNumXcd * ctx->n));
             if (pa)
@@ -1226,7 +1245,7 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
     const int64_t L = (int64_t)1 << pl.tile_log2;
     const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
     for (int32_t j0 = 0; j0 < ctx->r; j0 += pl.stage_rows) {
-        const RowGroup rg = {j0, (ctx->r - j0) < pl.stage_rows ? (ctx->r - j0) : pl.stage_rows, pl.stage_rows, ctx->r};
+        const RowGroup rg = {j0, (ctx->r - j0) < pl.stage_rows ? (ctx->r - j0) : pl.stage_rows, pl.stage_rows, ctx->r, pl.stage_ilv};
         if (j0 > 0 || pl.staged_u != u) {                            // not staged by a fused head: pass 1 now
             ProfScope ps(ctx, KID_BIN_SCATTER);
             hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd * ctx->n)), dim3((unsigned)g_tun.scatter_threads),
