@@ -104,6 +104,64 @@ def test_full_size_second_iteration_matches_oracle(wl, full_sort, sketch_workers
         sams.sams_configure("fuse_head", 0)
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("wl,P", [("C2", 4), ("P1", 8)])
+def test_full_size_variants_parameter_averaging_and_second_round(wl, P):
+    """The two variants bench.py can time (--variant pa, --overselect P), at a workload's full size and in
+    bench.py's launch configuration: one iteration of Alg. 1 with P*k candidates and the exact second round,
+    every output compared with the oracle fed with the GPU's inputs of that stage."""
+    from paper_2210_07454_amd import sams
+    w = inputs.WORKLOADS[wl]
+    d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
+    kc = P * k
+    sams.sams_configure("fuse_head", 2)
+    try:
+        gs = inputs.GradientStream(w, device="cuda")
+        hp = inputs.hash_params(r, seed=w.seed)
+        o = Oracle("f32")
+        with sams.Context(d, n, r, c, kc, hp) as ctx:
+            b = sams.Buffers(d, n, r, c, kc, w.eps, gs.x1())
+            vw = torch.full((n, d), w.eps, device="cuda")
+            vhw = torch.full((n, d), w.eps, device="cuda")
+            idx_f = torch.empty(k, device="cuda", dtype=torch.int32)
+            delta_f = torch.empty(k, device="cuda")
+            st = dict(m=np.zeros((n, d), np.float32), e=np.zeros((n, d), np.float32),
+                      vw=np.full((n, d), w.eps, np.float32), vhw=np.full((n, d), w.eps, np.float32), x=host(b.x).copy())
+            g1, g2 = gs.step(0), gs.step(1)
+            ctx.amsgrad_ef_update_pa(g1, b.m, b.e_u, vw, vhw, b.x, None, None, 0, w.beta1, w.beta2, w.lr)
+            o.head_pa(host(g1), st["m"], st["e"], st["vw"], st["vhw"], w.beta1, w.beta2)
+            for key, t in (("m", b.m), ("e", b.e_u), ("vw", vw), ("vhw", vhw)):
+                assert np.array_equal(host(t), st[key]), key
+            ctx.sketch_accumulate(b.e_u, b.S_workers)
+            S_w = host(b.S_workers)
+            for i in (0, n - 1):
+                assert np.array_equal(S_w[i], o.sketch(st["e"][i], hp, c)), ("sketch", i)
+            ctx.sketch_reduce(b.S_workers, b.S_mean)
+            S_mean = host(b.S_mean)
+            assert np.array_equal(S_mean, o.sketch_mean(S_w))
+            del S_w
+            ctx.unsketch_topk(b.S_mean, None, b.idx, None)            # Alg. 1: plain unsketch operator
+            est = o.unsketch(S_mean, None, d, hp)
+            cand = o.topk(est, kc)
+            assert np.array_equal(host(b.idx), cand)
+            ctx.gather_topk(b.e_u, None, b.idx, b.U_workers, b.delta)
+            U_w, dcand = o.gather(st["e"], None, cand)
+            assert np.array_equal(host(b.U_workers), U_w) and np.array_equal(host(b.delta), dcand)
+            ctx.topk_refine(b.idx, b.delta, k, idx_f, delta_f)
+            idx, delta = o.refine(cand, dcand, k)
+            assert np.array_equal(host(idx_f), idx) and np.array_equal(host(delta_f), delta)
+            # tail + the head of the next iteration, fused with the staging of its u
+            ctx.amsgrad_ef_update_pa(g2, b.m, b.e_u, vw, vhw, b.x, idx_f, delta_f, k, w.beta1, w.beta2, w.lr)
+            o.tail(st["e"], st["x"], idx, delta, w.lr)
+            o.head_pa(host(g2), st["m"], st["e"], st["vw"], st["vhw"], w.beta1, w.beta2)
+            for key, t in (("m", b.m), ("e", b.e_u), ("vw", vw), ("vhw", vhw), ("x", b.x)):
+                assert np.array_equal(host(t), st[key]), ("second head", key)
+            ctx.sketch_accumulate(b.e_u, b.S_workers)                 # from the staged copy
+            assert np.array_equal(host(b.S_workers[0]), o.sketch(st["e"][0], hp, c))
+    finally:
+        sams.sams_configure("fuse_head", 0)
+
+
 @pytest.mark.timeout(1500)
 def test_stress_size_second_iteration_sampled(capfd):
     """C5 (d = 1.3 G): the binned path with two sketch rows staged at a time so that state, plan and staging fit
