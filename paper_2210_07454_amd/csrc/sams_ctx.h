@@ -69,7 +69,8 @@ struct Plan {
     uint32_t *binbase;  // [r][nbins+1]     start of each bin in the row stream (multiples of the chunk)
     uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags
     uint16_t *wlow;     // [r][rowlen]          per stream position: bucket in window only (what the recovery reads)
-    float *stg;         // [n][r][rowlen]       per-step staging: signed values at their stream positions
+    float *stg;         // n * stage_rows * rowlen floats: per-step staging, signed values at their stream positions
+                        //                      ([stage_rows][rowlen/32][n][32], or [n][stage_rows][rowlen] without stage_ilv)
     const float *staged_u;  // vector whose sorted copy the staging holds (set by a fused head), else null
     float *rowest;      // [r][d]               per-step: signed row estimates in coordinate order (stage 3);
                         //                      absent when the median is fused (fused_median)
