@@ -5,10 +5,12 @@ A "step" is one pass of the whole hot path over one batch of synthetic gradients
 resident in HBM: sketch_accumulate -> sketch_reduce -> unsketch_topk -> gather_topk ->
 amsgrad_ef_update (which finishes the iteration and runs the dense moment update of the next one).
 Prints ONE JSON line: coords/s (= d / t_step), the HBM roofline of the dominant kernel measured with
-HIP events inside the timed region, the whole-step roofline fraction, and the CPU oracle timed on a
-bounded sample of the same workload.
+HIP events inside the timed region (the dominant kernel is found during the warm-up steps and is the only
+one bracketed by events while the K steps are timed; the per-kernel table comes from a separate pass of
+K steps afterwards), the whole-step roofline fraction, and the CPU oracle timed on a bounded sample of
+the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--variant pa] [--overselect P] [--graph]
 """
 from __future__ import annotations
 
@@ -104,6 +106,9 @@ def main():
                     help="P of the paper's second round: P*k candidates, then topk_refine (default 1: none)")
     ap.add_argument("--no-vram-precondition", action="store_true",
                     help="skip the allocate-and-free pass over the free device memory before the buffers are created")
+    ap.add_argument("--graph", action="store_true",
+                    help="time the K steps as one replay of a HIP graph captured from them (for small, launch-bound "
+                         "workloads); the per-kernel figures then come from an eager pass of K steps run before it")
     ap.add_argument("--tune", default="fuse_head=2",
                     help="library tunables (sams_configure), e.g. fuse_head=1,tile_log2=14,win_log2=15")
     args = ap.parse_args()
@@ -123,6 +128,9 @@ def main():
     P = max(1, args.overselect)
     kc = P * k                                   # candidates taken from the sketch
     torch.cuda.set_device(0)
+    # a graph cannot be captured from the default stream: then everything runs on a stream of its own
+    stream = torch.cuda.Stream() if args.graph else torch.cuda.current_stream()
+    torch.cuda.set_stream(stream)
     if not args.no_vram_precondition:
         # nearly all free device memory allocated once in 1 GiB blocks and given back, before any buffer of the
         # run exists: afterwards the library's buffers are placed so that the same kernels run 3-14 % faster
@@ -156,33 +164,63 @@ def main():
             ctx.topk_refine(b.idx, b.delta, k, idx_f, delta_f)
         update(pool[(t + 1) % len(pool)], idx_f, delta_f, k)
 
-    # head of the first iteration, then warm-up
+    # head of the first iteration, then warm-up; the warm-up steps are timed kernel by kernel to find the
+    # dominant kernel, which is then the only one bracketed by events inside the timed region (two event records
+    # per launch of every kernel cost the step about 2 % at C4, and more on small workloads)
     update(pool[0], None, None, 0)
     t = 0
-    for _ in range(args.warmup):
+    for q in range(args.warmup):
+        if q == min(1, args.warmup - 1):            # the first step carries one-time costs: not timed unless it is the only one
+            ctx.sams_profile_enable(True)
         one_step(t)
         t += 1
     torch.cuda.synchronize()
-
-    ctx.sams_profile_enable(True)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        one_step(t)
-        t += 1
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
     ctx.sams_profile_enable(False)
-    prof = ctx.sams_profile_read()
+    warm = ctx.sams_profile_read()
+    dom_name = max(warm.items(), key=lambda kv: kv[1][0])[0] if warm else None
+
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed_eager(only):
+        nonlocal t
+        ctx.sams_profile_only(only)
+        ctx.sams_profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(args.steps):
+            one_step(t)
+            t += 1
+        ev1.record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ctx.sams_profile_enable(False)
+        ctx.sams_profile_only(None)
+        return dt, ctx.sams_profile_read()
+
+    wall, prof = timed_eager(dom_name)
+    if args.graph:
+        # the same K steps, captured once (capture executes nothing) and replayed: one untimed replay, one timed
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for q in range(args.steps):
+                one_step(t + q)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
-    # dominant kernel: largest total device time inside the timed region
+    # dominant kernel: largest total device time (over the warm-up steps); its launches inside the timed region
     dom = max(prof.items(), key=lambda kv: kv[1][0])
     dom_name, (dom_ms, dom_n) = dom
+    # every kernel's share: a separate pass of K steps after the timed one, every launch bracketed
+    _, breakdown = timed_eager(None)
     avg_ms = dom_ms / dom_n
     kbytes = kernel_algorithmic_bytes(dom_name, d, n, r, c, k, pa)
     achieved = (kbytes / (avg_ms * 1e-3)) / 1e9 if kbytes else None
@@ -205,14 +243,15 @@ def main():
         "config": {"workload": f"{w.name}: d={d}, n={n} simulated workers, sketch {r}x{c}, k={k}, "
                                f"{w.noise} gradients in {w.nseg} segments + {w.heavy} heavy coordinates",
                    "d": d, "n": n, "r": r, "c": c, "k": k, "tunables": args.tune, "overselect_P": P, "variant": args.variant,
-                   "vram_preconditioned": not args.no_vram_precondition},
+                   "vram_preconditioned": not args.no_vram_precondition, "hip_graph": bool(args.graph)},
         "worker_coords_per_s": n * d / (ms_per_step * 1e-3),
         "device_ms_per_step": ev_ms_per_step,
         "step_algorithmic_bytes": step_bytes,
         "step_hbm_gbs": step_gbs,
         "step_roofline_frac": step_gbs / HBM_PEAK_GBS,
         "roofline": roofline,
-        "kernels_ms_per_step": {kn: round(v[0] / args.steps, 4) for kn, v in sorted(prof.items())},
+        "kernels_ms_per_step": {kn: round(v[0] / args.steps, 4) for kn, v in sorted(breakdown.items())},
+        "kernels_ms_per_step_from": f"a separate pass of {args.steps} steps after the timed region, every launch bracketed by events",
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_d)

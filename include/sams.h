@@ -139,6 +139,9 @@ int sams_last_hip_error(void);
  *   sams_profile_kernels   number of distinct kernels the library can launch
  *   sams_profile_name      name of kernel `kernel` (0 <= kernel < sams_profile_kernels()), static string
  *   sams_profile_enable    on != 0: clear the totals and start a window; on == 0: stop recording
+ *   sams_profile_only      restricts the timing to one kernel (kernel = its index; -1 = every kernel, the default),
+ *                          so that a timed region carries two event records per step instead of two per launch;
+ *                          takes effect from the next launch
  *   sams_profile_read      waits for the stream, then writes, per kernel, the summed duration in
  *                          milliseconds and the number of timed launches since the window started
  *                          (total_ms, launches: HOST arrays of sams_profile_kernels() elements)
@@ -146,6 +149,7 @@ int sams_last_hip_error(void);
 int sams_profile_kernels(void);
 const char *sams_profile_name(int kernel);
 int sams_profile_enable(sams_ctx *ctx, int on);
+int sams_profile_only(sams_ctx *ctx, int kernel);
 int sams_profile_read(sams_ctx *ctx, double *total_ms, int64_t *launches);
 
 /*

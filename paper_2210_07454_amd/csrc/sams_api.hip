@@ -92,6 +92,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
     memset(ctx, 0, sizeof(*ctx));
     ctx->d = d; ctx->n = n; ctx->r = r; ctx->c = c; ctx->k = k;
     ctx->stream = (hipStream_t)hip_stream;
+    ctx->prof_only = -1;
     ctx->hp.r = r;
     ctx->hp.modc = make_modc((uint32_t)c);
     for (int j = 0; j < r; ++j) {
@@ -258,6 +259,13 @@ int sams_profile_enable(sams_ctx *ctx, int on)
     } else {
         ctx->prof_on = 0;
     }
+    return SAMS_OK;
+}
+
+int sams_profile_only(sams_ctx *ctx, int kernel)
+{
+    if (!ctx || kernel < -1 || kernel >= KID_COUNT) return SAMS_EINVAL;
+    ctx->prof_only = kernel;
     return SAMS_OK;
 }
 

@@ -113,6 +113,7 @@ struct sams_ctx {
     sams::Plan plan;
     // per-kernel timing (host)
     int prof_on;
+    int prof_only;           // kernel id the timing is restricted to, -1 = every kernel
     int prof_used;
     sams::ProfRec *prof;     // [kProfPool], events created on first enable
     double prof_ms[sams::KID_COUNT];
@@ -137,7 +138,7 @@ struct ProfScope {
     int slot;
     ProfScope(sams_ctx *c, int kid) : ctx(c), slot(-1)
     {
-        if (c->prof_on && c->prof_used < kProfPool) {
+        if (c->prof_on && (c->prof_only < 0 || c->prof_only == kid) && c->prof_used < kProfPool) {
             slot = c->prof_used++;
             c->prof[slot].kid = kid;
             (void)hipEventRecord(c->prof[slot].a, c->stream);

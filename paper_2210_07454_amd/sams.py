@@ -21,7 +21,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 
 # every symbol include/sams.h declares
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_precondition_device_memory", "sams_last_hip_error", "sams_hash_dump",
-           "sams_configure", "sams_sketch_mode", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_read",
+           "sams_configure", "sams_sketch_mode", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_only", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk", "topk_refine",
            "amsgrad_ef_update", "amsgrad_ef_update_pa"]
 
@@ -60,6 +60,7 @@ def load() -> ctypes.CDLL:
     lib.sams_profile_kernels.argtypes = []
     lib.sams_profile_name.argtypes = [ctypes.c_int]
     lib.sams_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.sams_profile_only.argtypes = [vp, ctypes.c_int]
     lib.sams_profile_read.argtypes = [vp, vp, vp]
     lib.sketch_accumulate.argtypes = [vp, vp, vp]
     lib.sketch_reduce.argtypes = [vp, vp, vp]
@@ -153,6 +154,12 @@ class Context:
 
     def sams_profile_enable(self, on: bool):
         _check(self._lib.sams_profile_enable(self._h, 1 if on else 0), "sams_profile_enable")
+
+    def sams_profile_only(self, name=None):
+        """Restrict the timing to the kernel called ``name`` (None: every kernel)."""
+        nk = self._lib.sams_profile_kernels()
+        names = [self._lib.sams_profile_name(q).decode() for q in range(nk)]
+        _check(self._lib.sams_profile_only(self._h, -1 if name is None else names.index(name)), "sams_profile_only")
 
     def sams_profile_read(self):
         """{kernel name: (total milliseconds, launches)} since profiling was enabled."""
