@@ -608,3 +608,47 @@ def test_step_on_a_side_stream_and_as_a_replayed_hip_graph(sams):
     ctx_g.close()
     for key, val in PATHS["default"].items():
         sams.sams_configure(key, val)
+
+
+def test_kernel_timing_counts_launches_and_changes_no_result(sams):
+    """The optional per-kernel timing: every launch of the window is counted once, a filter restricts it to one
+    kernel, durations are positive, and the outputs are the same bits as without it."""
+    d, n, r, c, k = 100_003, 3, 5, 1_000, 777
+    rng = np.random.default_rng(5)
+    hp = inputs.hash_params(r, seed=5)
+    u = dev(rng.standard_normal((n, d)).astype(np.float32))
+    with sams.Context(d, n, r, c, k, hp) as ctx:
+        S = torch.empty((n, r, c), device="cuda")
+        S_mean = torch.empty((r, c), device="cuda")
+        idx = torch.empty(k, device="cuda", dtype=torch.int32)
+
+        def run():
+            ctx.sketch_accumulate(u, S)
+            ctx.sketch_reduce(S, S_mean)
+            ctx.unsketch_topk(S_mean, None, idx, None)
+            return host(S).copy(), host(S_mean).copy(), host(idx).copy()
+
+        plain = run()
+        ctx.sams_profile_enable(True)
+        timed = [run() for _ in range(3)]
+        ctx.sams_profile_enable(False)
+        prof = ctx.sams_profile_read()
+        for got in timed:
+            assert all(np.array_equal(a, b) for a, b in zip(got, plain))
+        assert prof["k_reduce"][1] == 3 and prof["k_sel_hist"][1] == 9 and prof["k_sel_write"][1] == 3
+        assert all(ms > 0.0 for ms, _ in prof.values())
+        ctx.sams_profile_only("k_reduce")
+        ctx.sams_profile_enable(True)
+        run()
+        run()
+        ctx.sams_profile_enable(False)
+        only = ctx.sams_profile_read()
+        assert set(only) == {"k_reduce"} and only["k_reduce"][1] == 2
+        ctx.sams_profile_only(None)
+        ctx.sams_profile_enable(True)
+        run()
+        ctx.sams_profile_enable(False)
+        assert len(ctx.sams_profile_read()) > 3
+        before = ctx.sams_profile_read()
+        run()                                                        # switched off: nothing more is recorded
+        assert ctx.sams_profile_read() == before
