@@ -166,7 +166,7 @@ def main():
 
     # head of the first iteration, then warm-up; the warm-up steps are timed kernel by kernel to find the
     # dominant kernel, which is then the only one bracketed by events inside the timed region (two event records
-    # per launch of every kernel cost the step about 2 % at C4, and more on small workloads)
+    # per launch of every kernel double the step time of the small workloads)
     update(pool[0], None, None, 0)
     t = 0
     for q in range(args.warmup):
