@@ -66,8 +66,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
  * fp32 additions inside a bucket).  Keys:
  *   "tile_log2"   0 or 6..14 (default 0): log2 of the coordinates per tile of the binned sketch path.  0 = chosen
- *                 from r and d: 2^14 (2^13 for r > 6, 2^12 for r > 12), or less (down to 2^8) while the vector
- *                 has fewer tiles than the chip has compute units
+ *                 from r, d, n: 2^14 (2^13 for r > 6, 2^12 for r > 12), or less (down to 2^8) while the first pass
+ *                 would have too few workgroups to fill the chip (it has one per tile with "fuse_head" 1, one per
+ *                 (tile, worker) otherwise)
  *   "win_log2"    0 or 4..15 (default 0): log2 of the buckets per LDS window (the bins of the binned path; a
  *                 table with c <= 2^win_log2 is a single bin, see "sketch_path").  0 = chosen from n, r, c:
  *                 2^15, or less (down to 2^12) when that is needed to give the chip enough windows to work on

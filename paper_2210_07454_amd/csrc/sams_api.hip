@@ -15,7 +15,7 @@ static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
     "k_estimate", "k_sel_init", "k_sel_hist", "k_sel_pick", "k_sel_count", "k_sel_scan", "k_sel_write",
     "k_gather", "k_plan_build", "k_bin_scatter", "k_bin_accumulate", "k_sketch_lds", "k_bin_lookup",
-    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map", "k_head_pa", "k_head_sparse_v"};
+    "k_bin_collect", "k_est_median", "k_head_scatter", "k_refine_map", "k_head_pa", "k_head_sparse_v", "k_sel_small"};
 
 const char *kernel_name(int kid) { return (kid >= 0 && kid < KID_COUNT) ? kKernelNames[kid] : ""; }
 
@@ -79,7 +79,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
     if (!out) return SAMS_EINVAL;
     *out = nullptr;
     if (!hash_host) return SAMS_EINVAL;
-    if (d < 1 || d >= (int64_t)kP31 || n < 1 || n > 1024 || r < 1 || r > SAMS_MAX_ROWS || c < 1 ||
+    if (d < 1 || d >= (int64_t)kP31 || n < 1 || n > kMaxWorkers || r < 1 || r > SAMS_MAX_ROWS || c < 1 ||
         c >= (int64_t)kP31 || k < 1 || k > d)
         return SAMS_EINVAL;
     for (int j = 0; j < r; ++j) {

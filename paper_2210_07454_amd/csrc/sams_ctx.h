@@ -30,6 +30,8 @@ constexpr int kWave = 64;
 constexpr int kSelTile = 8192;      // coordinates one wavefront compacts in the selection
 constexpr int kHistBins = 2048;     // first radix digit: 11 bits, then 10 and 10
 constexpr int kSelPasses = 3;
+constexpr int kSelSmallSeg = 4096;   // keys per wavefront of the one-workgroup selection ...
+constexpr int kSelSmallMax = 16 * kSelSmallSeg;   // ... which handles up to this many keys
 
 // device-resident state of the radix selection (no host round trip inside a step)
 struct SelState {
@@ -44,10 +46,13 @@ enum KernelId {
     KID_FILL = 0, KID_HASH_DUMP, KID_TAIL_X, KID_TAIL_ZERO_E, KID_HEAD, KID_SKETCH_ATOMIC, KID_REDUCE,
     KID_ESTIMATE, KID_SEL_INIT, KID_SEL_HIST, KID_SEL_PICK, KID_SEL_COUNT, KID_SEL_SCAN, KID_SEL_WRITE,
     KID_GATHER, KID_PLAN_BUILD, KID_BIN_SCATTER, KID_BIN_ACCUMULATE, KID_SKETCH_LDS, KID_BIN_LOOKUP,
-    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_HEAD_PA, KID_HEAD_SPARSE_V, KID_COUNT
+    KID_BIN_COLLECT, KID_EST_MEDIAN, KID_HEAD_SCATTER, KID_REFINE_MAP, KID_HEAD_PA, KID_HEAD_SPARSE_V, KID_SEL_SMALL, KID_COUNT
 };
 const char *kernel_name(int kid);
 
+constexpr int kMaxWorkers = 1024;     // n accepted by sams_create
+constexpr int kWideCoords = 8;        // coordinates per workgroup of the 32-lanes-per-coordinate sparse kernels
+constexpr int kWideMinWorkers = 16;   // ... which are used from this many workers on
 constexpr int kProfPool = 8192;   // event pairs kept for one profiling window
 
 struct ProfRec {

@@ -603,12 +603,44 @@ k_head_sparse_v(const float *__restrict__ g, const int32_t *__restrict__ idx, in
     const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
     if (q >= k_sel) return;
     const int64_t l = idx[q];
-    float gs = g[l];
-    for (int32_t i = 1; i < n; ++i) gs = (gs + g[(int64_t)i * d + l]);
+    float gs = 0.0f;
+    for (int32_t i0 = 0; i0 < n; i0 += 8) {                          // eight loads in flight, added in worker order
+        float val[8];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) {
+            const int32_t i = (i0 + z < n) ? (i0 + z) : (n - 1);
+            val[z] = g[(int64_t)i * d + l];
+        }
+#pragma unroll
+        for (int z = 0; z < 8; ++z)
+            if (i0 + z < n) gs = (i0 + z == 0) ? val[z] : (gs + val[z]);
+    }
     const float h = (gs / (float)n);
     const float vv = (v[l] + (omb2 * (h * h)));
     v[l] = vv;
     if (vv > vhat[l]) vhat[l] = vv;
+}
+
+// the same with 32 lanes per coordinate for many workers (see k_gather_wide)
+__global__ void __launch_bounds__(256)
+k_head_sparse_v_wide(const float *__restrict__ g, const int32_t *__restrict__ idx, int64_t k_sel, int32_t n,
+                     int64_t d, float omb2, float *__restrict__ v, float *__restrict__ vhat)
+{
+    __shared__ float vals[kWideCoords * kMaxWorkers];
+    const int ql = threadIdx.x >> 5, wl = threadIdx.x & 31;
+    const int64_t q = blockIdx.x * (int64_t)kWideCoords + ql;
+    const int64_t l = q < k_sel ? idx[q] : 0;
+    if (q < k_sel)
+        for (int32_t i = wl; i < n; i += 32) vals[ql * n + i] = g[(int64_t)i * d + l];
+    __syncthreads();
+    if (q < k_sel && wl == 0) {
+        float gs = vals[ql * n];
+        for (int32_t i = 1; i < n; ++i) gs = (gs + vals[ql * n + i]);
+        const float h = (gs / (float)n);
+        const float vv = (v[l] + (omb2 * (h * h)));
+        v[l] = vv;
+        if (vv > vhat[l]) vhat[l] = vv;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1010,10 +1042,14 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.tile_log2 = tun.tile_log2;
     if (pl.tile_log2 == 0) {
         // automatic tile: 2^14 coordinates (2^13 above 6 rows, 2^12 above 12, so that a thread can keep the row
-        // estimates of its coordinates in registers for the median), halved (down to 2^8) while that leaves fewer
-        // tiles than compute units -- one workgroup per tile carries pass 1 and the dense update
+        // estimates of its coordinates in registers for the median), halved (down to 2^8) while pass 1 and the
+        // dense update would have too few workgroups for the chip's 256 compute units: one per tile with
+        // fuse_head = 1 (at least 256 wanted), one per (tile, worker) otherwise (at least 1024 wanted, the
+        // recovery still has one per tile)
         pl.tile_log2 = ctx->r <= 6 ? 14 : (ctx->r <= 12 ? 13 : 12);
-        while (pl.tile_log2 > 8 && ((ctx->d + ((int64_t)1 << pl.tile_log2) - 1) >> pl.tile_log2) < 256) --pl.tile_log2;
+        const int64_t per_tile = tun.fuse_head == 1 ? 1 : ctx->n, want = tun.fuse_head == 1 ? 256 : 1024;
+        while (pl.tile_log2 > 8 && ((ctx->d + ((int64_t)1 << pl.tile_log2) - 1) >> pl.tile_log2) * per_tile < want)
+            --pl.tile_log2;
     }
     if (pl.win_log2 == 0) {
         // automatic window: the largest one (longest runs, least padding) that still leaves about eight
@@ -1215,9 +1251,14 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
                                pl.rowlen);
     }
-    if (g_tun.fuse_head == 2 && !pa && k_prev > 0)
-        SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v, (unsigned)((k_prev + 255) / 256), 256, g, idx_prev, k_prev,
-                    ctx->n, ctx->d, 1.0f - beta2, v, vhat);
+    if (g_tun.fuse_head == 2 && !pa && k_prev > 0) {
+        if (ctx->n >= kWideMinWorkers)
+            SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_wide, (unsigned)((k_prev + kWideCoords - 1) / kWideCoords),
+                        256, g, idx_prev, k_prev, ctx->n, ctx->d, 1.0f - beta2, v, vhat);
+        else
+            SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v, (unsigned)((k_prev + 255) / 256), 256, g, idx_prev,
+                        k_prev, ctx->n, ctx->d, 1.0f - beta2, v, vhat);
+    }
     SAMS_HIP(hipGetLastError());
     pl.staged_u = e_u;          // the staging now holds the sorted copy of this vector
     return SAMS_OK;

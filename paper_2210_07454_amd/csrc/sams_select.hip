@@ -175,18 +175,12 @@ k_sel_pick(SelState *st, uint32_t *hist, int pass)
     }
 }
 
-// per wavefront tile of kSelTile consecutive coordinates: how many keys exceed tau, how many equal it
-__global__ void __launch_bounds__(256)
-k_sel_count(const float *__restrict__ est, int64_t d, const SelState *__restrict__ st,
-            uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq, int64_t ntile)
+// one wavefront over the keys [base, base + span): how many exceed tau, how many equal it (in every lane)
+__device__ __forceinline__ void wave_count(const float *__restrict__ est, int64_t d, int64_t base, int span,
+                                           uint32_t tau, int lane, uint32_t *gt_out, uint32_t *eq_out)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    int64_t tile = blockIdx.x * (int64_t)(blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (tile >= ntile) return;
-    const uint32_t tau = st->tau;
-    int64_t base = tile * kSelTile;
     uint32_t ngt = 0, neq = 0;                                       // this lane's counts
-    for (int s = 0; s < kSelTile; s += kWave * 4) {
+    for (int s = 0; s < span; s += kWave * 4) {
         const Keys4 q = load_keys4(est, base + s + lane * 4, d);
 #pragma unroll
         for (int z = 0; z < 4; ++z) {
@@ -201,6 +195,20 @@ k_sel_count(const float *__restrict__ est, int64_t d, const SelState *__restrict
         ngt += __shfl_xor(ngt, off);
         neq += __shfl_xor(neq, off);
     }
+    *gt_out = ngt;
+    *eq_out = neq;
+}
+
+// per wavefront tile of kSelTile consecutive coordinates: how many keys exceed tau, how many equal it
+__global__ void __launch_bounds__(256)
+k_sel_count(const float *__restrict__ est, int64_t d, const SelState *__restrict__ st,
+            uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq, int64_t ntile)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int64_t tile = blockIdx.x * (int64_t)(blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (tile >= ntile) return;
+    uint32_t ngt, neq;
+    wave_count(est, d, tile * kSelTile, kSelTile, st->tau, lane, &ngt, &neq);
     if (lane == 0) {
         cnt_gt[tile] = ngt;
         cnt_eq[tile] = neq;
@@ -241,21 +249,14 @@ k_sel_scan(const uint32_t *__restrict__ cnt_gt, const uint32_t *__restrict__ cnt
     }
 }
 
-// ordered compaction: every wavefront walks its tile in index order and writes the selected
-// coordinates (key > tau, or key == tau and among the first k_eq such coordinates) at their rank
-__global__ void __launch_bounds__(256)
-k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict__ st,
-            const uint32_t *__restrict__ sel_base, const uint32_t *__restrict__ eq_base,
-            int64_t ntile, int64_t k, int32_t *__restrict__ idx, float *__restrict__ est_sel)
+// one wavefront walks the keys [base, base + span) in index order and writes the selected ones (key > tau, or
+// key == tau and among the first k_eq such keys) at their rank; out, eqr: selected and equal keys before base
+__device__ __forceinline__ void wave_compact(const float *__restrict__ est, int64_t d, int64_t base, int span,
+                                             uint32_t tau, uint32_t k_eq, int lane, uint32_t out, uint32_t eqr,
+                                             int64_t k, int32_t *__restrict__ idx, float *__restrict__ est_sel)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    int64_t tile = blockIdx.x * (int64_t)(blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (tile >= ntile) return;
-    const uint32_t tau = st->tau, k_eq = st->k_eq;
-    int64_t base = tile * kSelTile;
-    uint32_t out = sel_base[tile], eqr = eq_base[tile];
     const uint64_t below = ((uint64_t)1 << lane) - 1;
-    for (int s = 0; s < kSelTile; s += kWave * 4) {
+    for (int s = 0; s < span; s += kWave * 4) {
         const int64_t l0 = base + s + lane * 4;                      // this lane's four consecutive keys
         const Keys4 q = load_keys4(est, l0, d);
         uint32_t gt = 0, eq = 0;                                     // bit z: key z is above / at the threshold
@@ -289,6 +290,92 @@ k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict
         out += take_total;
         eqr += eq_total;
     }
+}
+
+// ordered compaction: every wavefront walks its tile in index order and writes the selected
+// coordinates (key > tau, or key == tau and among the first k_eq such coordinates) at their rank
+__global__ void __launch_bounds__(256)
+k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict__ st,
+            const uint32_t *__restrict__ sel_base, const uint32_t *__restrict__ eq_base,
+            int64_t ntile, int64_t k, int32_t *__restrict__ idx, float *__restrict__ est_sel)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int64_t tile = blockIdx.x * (int64_t)(blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (tile >= ntile) return;
+    wave_compact(est, d, tile * kSelTile, kSelTile, st->tau, st->k_eq, lane, sel_base[tile], eq_base[tile], k, idx,
+                 est_sel);
+}
+
+// The whole selection in one workgroup of 1024 threads for len <= kSelSmallMax keys: the three histogram passes
+// with their digit picks, the counts per segment of kSelSmallSeg keys (one wavefront each), their prefixes, and
+// the ordered compaction.  Same arithmetic as the kernels above; replaces ten launches, which is most of the
+// step's time when the vector has only tens of thousands of coordinates.
+__global__ void __launch_bounds__(1024)
+k_sel_small(const float *__restrict__ keys, int64_t len, uint32_t k, int32_t *__restrict__ idx,
+            float *__restrict__ val_sel)
+{
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ uint32_t part[1024];
+    __shared__ uint32_t sh[2];                                       // prefix, k_rem after a pick
+    __shared__ uint32_t seg_gt[16], seg_eq[16], seg_sel_base[16], seg_eq_base[16];
+    const int t = threadIdx.x;
+    uint32_t prefix = 0, k_rem = k;
+    for (int pass = 0; pass < kSelPasses; ++pass) {
+        const int shift = sel_shift(pass), width = sel_width(pass);
+        const uint32_t dmask = (1u << width) - 1u;
+        for (int b = t; b < kHistBins; b += 1024) lh[b] = 0;
+        __syncthreads();
+        for (int64_t l = (int64_t)t * 4; l < len; l += 4096) {
+            const Keys4 q = load_keys4(keys, l, len);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const uint32_t key = mag_key(q.v[z]);
+                if (((q.have >> z) & 1u) && (key >> (shift + width)) == prefix)
+                    atomicAdd(&lh[(key >> shift) & dmask], 1u);
+            }
+        }
+        __syncthreads();
+        const int nb = 1 << width;
+        const int b0 = nb - 1 - 2 * t, b1 = nb - 2 - 2 * t;          // descending bins, two per thread
+        const uint32_t v0 = b0 >= 0 ? lh[b0] : 0u, v1 = b1 >= 0 ? lh[b1] : 0u;
+        const uint32_t above0 = block_exclusive_scan_1024(v0 + v1, part), above1 = above0 + v0;
+        int b = -1;
+        uint32_t above = 0;
+        if (b0 >= 0 && above0 < k_rem && k_rem <= above0 + v0) { b = b0; above = above0; }
+        if (b1 >= 0 && above1 < k_rem && k_rem <= above1 + v1) { b = b1; above = above1; }
+        if (b >= 0) {                                                // exactly one thread, since k_rem <= total
+            sh[0] = (prefix << width) | (uint32_t)b;
+            sh[1] = k_rem - above;
+        }
+        __syncthreads();
+        prefix = sh[0];
+        k_rem = sh[1];
+        __syncthreads();
+    }
+    const uint32_t tau = prefix, k_eq = k_rem;
+    const int lane = t & (kWave - 1), seg = t / kWave;               // 16 wavefronts, one segment each
+    const int64_t base = (int64_t)seg * kSelSmallSeg;
+    uint32_t ngt = 0, neq = 0;
+    if (base < len) wave_count(keys, len, base, kSelSmallSeg, tau, lane, &ngt, &neq);
+    if (lane == 0) {
+        seg_gt[seg] = ngt;
+        seg_eq[seg] = neq;
+    }
+    __syncthreads();
+    if (t == 0) {
+        uint32_t eb = 0, sb = 0;
+        for (int q = 0; q < 16; ++q) {
+            seg_eq_base[q] = eb;
+            seg_sel_base[q] = sb;
+            const uint32_t want = eb < k_eq ? k_eq - eb : 0u;
+            sb += seg_gt[q] + (seg_eq[q] < want ? seg_eq[q] : want);
+            eb += seg_eq[q];
+        }
+    }
+    __syncthreads();
+    if (base < len)
+        wave_compact(keys, len, base, kSelSmallSeg, tau, k_eq, lane, seg_sel_base[seg], seg_eq_base[seg], (int64_t)k, idx,
+                     val_sel);
 }
 
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est)
@@ -345,6 +432,11 @@ k_refine_map(const int32_t *__restrict__ idx_in, const int32_t *__restrict__ pos
 // the k entries of keys[0..len) with the largest magnitude, ties to the smaller position; positions ascending
 int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel)
 {
+    if (len <= kSelSmallMax) {
+        SAMS_LAUNCH(ctx, KID_SEL_SMALL, k_sel_small, 1, 1024, keys, len, (uint32_t)k, idx, val_sel);
+        SAMS_HIP(hipGetLastError());
+        return SAMS_OK;
+    }
     const int64_t nt = (len + kSelTile - 1) / kSelTile;               // <= ctx->ntile since len <= d
     uint32_t *cnt_gt = ctx->cnt, *cnt_eq = ctx->cnt + ctx->ntile;
     uint32_t *sel_base = ctx->base, *eq_base = ctx->base + ctx->ntile;

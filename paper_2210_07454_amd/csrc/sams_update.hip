@@ -103,12 +103,22 @@ k_reduce(const float *__restrict__ S_w, float *__restrict__ S_mean, int32_t n, i
     for (; t < rc; t += st) {
         if constexpr (VEC == 4) {
             float4 acc = *reinterpret_cast<const float4 *>(S_w + t);
-            for (int32_t i = 1; i < n; ++i) {
-                const float4 b = *reinterpret_cast<const float4 *>(S_w + (int64_t)i * rc + t);
-                acc.x = (acc.x + b.x);
-                acc.y = (acc.y + b.y);
-                acc.z = (acc.z + b.z);
-                acc.w = (acc.w + b.w);
+            for (int32_t i0 = 1; i0 < n; i0 += 8) {                  // eight tables' loads in flight, added in worker order
+                float4 b[8];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) {
+                    const int32_t i = (i0 + z < n) ? (i0 + z) : (n - 1);
+                    b[z] = *reinterpret_cast<const float4 *>(S_w + (int64_t)i * rc + t);
+                }
+#pragma unroll
+                for (int z = 0; z < 8; ++z) {
+                    if (i0 + z < n) {
+                        acc.x = (acc.x + b[z].x);
+                        acc.y = (acc.y + b[z].y);
+                        acc.z = (acc.z + b[z].z);
+                        acc.w = (acc.w + b[z].w);
+                    }
+                }
             }
             *reinterpret_cast<float4 *>(S_mean + t) = make_float4((acc.x / fn), (acc.y / fn), (acc.z / fn), (acc.w / fn));
         } else {
@@ -130,13 +140,52 @@ k_gather(const float *__restrict__ u, const float *__restrict__ vhat, const int3
     if (q >= k) return;
     int64_t l = idx[q];
     float acc = 0.0f;
-    for (int32_t i = 0; i < n; ++i) {
-        float val = u[(int64_t)i * d + l];
-        U_w[(int64_t)i * k + q] = val;
-        acc = (i == 0) ? val : (acc + val);
+    // eight workers' values are fetched before the first is used (with many workers and few coordinates the
+    // kernel is a chain of memory latencies otherwise); they are still added in worker order
+    for (int32_t i0 = 0; i0 < n; i0 += 8) {
+        float val[8];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) {
+            const int32_t i = (i0 + z < n) ? (i0 + z) : (n - 1);
+            val[z] = u[(int64_t)i * d + l];
+        }
+#pragma unroll
+        for (int z = 0; z < 8; ++z) {
+            if (i0 + z < n) {
+                U_w[(int64_t)(i0 + z) * k + q] = val[z];
+                acc = (i0 + z == 0) ? val[z] : (acc + val[z]);
+            }
+        }
     }
     float mean = (acc / (float)n);
     delta[q] = vhat ? (mean / sqrtf(vhat[l])) : mean;
+}
+
+// The same for many workers: 32 lanes share a coordinate and fetch its n values side by side; they meet in LDS
+// and one lane adds them in worker order.  With n in the tens and k in the hundreds the one-thread-per-
+// coordinate kernel is a chain of n memory latencies on a handful of compute units.
+__global__ void __launch_bounds__(256)
+k_gather_wide(const float *__restrict__ u, const float *__restrict__ vhat, const int32_t *__restrict__ idx,
+              int64_t k, int32_t n, int64_t d, float *__restrict__ U_w, float *__restrict__ delta)
+{
+    __shared__ float vals[kWideCoords * kMaxWorkers];
+    const int ql = threadIdx.x >> 5, wl = threadIdx.x & 31;
+    const int64_t q = blockIdx.x * (int64_t)kWideCoords + ql;
+    const int64_t l = q < k ? idx[q] : 0;
+    if (q < k) {
+        for (int32_t i = wl; i < n; i += 32) {
+            const float val = u[(int64_t)i * d + l];
+            U_w[(int64_t)i * k + q] = val;
+            vals[ql * n + i] = val;
+        }
+    }
+    __syncthreads();
+    if (q < k && wl == 0) {
+        float acc = vals[ql * n];
+        for (int32_t i = 1; i < n; ++i) acc = (acc + vals[ql * n + i]);
+        const float mean = (acc / (float)n);
+        delta[q] = vhat ? (mean / sqrtf(vhat[l])) : mean;
+    }
 }
 
 // Head of Alg. 1 (parameter averaging): per-worker second moments, u = m / sqrt(vhat) + rho * e.
@@ -248,8 +297,12 @@ int enqueue_reduce(sams_ctx *ctx, const float *S_workers, float *S_mean)
 int enqueue_gather(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx,
                    float *U_workers, float *delta)
 {
-    SAMS_LAUNCH(ctx, KID_GATHER, k_gather, grid_for(ctx->k, 256), 256, u, vhat, idx, ctx->k, ctx->n,
-                ctx->d, U_workers, delta);
+    if (ctx->n >= kWideMinWorkers)
+        SAMS_LAUNCH(ctx, KID_GATHER, k_gather_wide, (unsigned)((ctx->k + kWideCoords - 1) / kWideCoords), 256, u, vhat,
+                    idx, ctx->k, ctx->n, ctx->d, U_workers, delta);
+    else
+        SAMS_LAUNCH(ctx, KID_GATHER, k_gather, grid_for(ctx->k, 256), 256, u, vhat, idx, ctx->k, ctx->n,
+                    ctx->d, U_workers, delta);
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
 }

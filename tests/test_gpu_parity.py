@@ -112,6 +112,8 @@ SHAPES = [  # d, n, r, c, k  -- several tiles, ragged tails, non-power-of-two c,
     (5_000, 2, 16, 7, 5_000),
     (262_144, 8, 7, 100_000, 3_000),
     (4_100, 5, 3, 8_191, 1),
+    (9_001, 19, 4, 300, 777),                     # many workers: the sparse kernels take 32 lanes per coordinate
+    (3_000, 33, 2, 64, 13),
 ]
 
 
