@@ -817,6 +817,8 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
 // k_bin_collect with the median of Sec. II-C and the 1/sqrt(vhat) scaling of Alg. 3 fused in: each thread
 // keeps the R row estimates of its 4 * ITERS coordinates in registers (tiles of at most 4096 * ITERS
 // coordinates), so the per-row estimates never go to memory.
+constexpr int kCollectAhead = 3;
+
 template <int R, int ITERS>
 __global__ void __launch_bounds__(kFusedThreads)
 k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ srcp,
@@ -829,24 +831,53 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
     const int64_t tile = blockIdx.x;
     const int64_t l0 = tile << tile_log2;
     float a[R][ITERS][4];
-#pragma unroll
-    for (int j = 0; j < R; ++j) {
-        float *buf = rowbuf + (j & 1) * L;
-        const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
+    // The loads of a row's first kCollectAhead sweeps are issued before the barrier of the row before it, so that
+    // they are in flight while the workgroup (the only one on its compute unit) waits and empties the LDS buffer.
+    // Past the tile's last slot group they read that group again (in bounds; not used).
+    uint2 pk[kCollectAhead];
+    float4 pv[kCollectAhead];
+    uint32_t o0 = 0, o1 = 0;
+    auto issue = [&](int j) {
+        o0 = pbase[(int64_t)j * (ntile + 1) + tile];
+        o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
         const uint16_t *sj = srcp + (int64_t)j * rowlen;
         const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
         const float *lj = lk + (int64_t)j * rowlen;
-        for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
-            const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-            const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
-            const float4 v = load_stream(reinterpret_cast<const float4 *>(lj + at));
-            const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
-                           s3 = packed.y >> 16;
-            if (s0 != kSrcPad) buf[s0 & 0x7fffu] = (s0 & 0x8000u) ? -v.x : v.x;
-            if (s1 != kSrcPad) buf[s1 & 0x7fffu] = (s1 & 0x8000u) ? -v.y : v.y;
-            if (s2 != kSrcPad) buf[s2 & 0x7fffu] = (s2 & 0x8000u) ? -v.z : v.z;
-            if (s3 != kSrcPad) buf[s3 & 0x7fffu] = (s3 & 0x8000u) ? -v.w : v.w;
+#pragma unroll
+        for (int s = 0; s < kCollectAhead; ++s) {
+            const uint32_t o = o0 + (uint32_t)(s * kFusedThreads + (int)threadIdx.x) * 4u;
+            const uint32_t oc = o < o1 ? o : o1 - 4u;                // a tile has at least one group of 16 slots
+            pk[s] = *reinterpret_cast<const uint2 *>(sj + oc);
+            pv[s] = load_stream(reinterpret_cast<const float4 *>(lj + dj[oc / kRunPad] + (oc & (kRunPad - 1))));
         }
+    };
+    auto place = [&](float *buf, const uint2 packed, const float4 v) {
+        const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu, s3 = packed.y >> 16;
+        if (s0 != kSrcPad) buf[s0 & 0x7fffu] = (s0 & 0x8000u) ? -v.x : v.x;
+        if (s1 != kSrcPad) buf[s1 & 0x7fffu] = (s1 & 0x8000u) ? -v.y : v.y;
+        if (s2 != kSrcPad) buf[s2 & 0x7fffu] = (s2 & 0x8000u) ? -v.z : v.z;
+        if (s3 != kSrcPad) buf[s3 & 0x7fffu] = (s3 & 0x8000u) ? -v.w : v.w;
+    };
+    issue(0);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        float *buf = rowbuf + (j & 1) * L;
+        const uint32_t b0 = o0, b1 = o1;
+#pragma unroll
+        for (int s = 0; s < kCollectAhead; ++s)
+            if (b0 + (uint32_t)(s * kFusedThreads + (int)threadIdx.x) * 4u < b1) place(buf, pk[s], pv[s]);
+        {
+            const uint16_t *sj = srcp + (int64_t)j * rowlen;
+            const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+            const float *lj = lk + (int64_t)j * rowlen;
+            for (uint32_t o = b0 + (uint32_t)(kCollectAhead * kFusedThreads + (int)threadIdx.x) * 4u; o < b1;
+                 o += kFusedThreads * 4) {
+                const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
+                const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+                place(buf, packed, load_stream(reinterpret_cast<const float4 *>(lj + at)));
+            }
+        }
+        if (j + 1 < R) issue(j + 1);
         __syncthreads();   // the other buffer is free again once every thread has passed this barrier
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
