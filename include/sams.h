@@ -94,6 +94,8 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 positions lie next to each other (one 128-byte line each), so that the workgroups of the workers,
  *                 which run side by side, write and read one region per (row, window) instead of n distant ones;
  *                 0: one contiguous copy per (worker, row).  Same results either way.
+ *   "acc_wide"    1 (default) or 0: with 1024 threads and 2048-position chunks the binned accumulation reads its two
+ *                 streams with 16-byte loads (half of the workgroup each) instead of 4-byte loads.  Same results.
  *   "fuse_median" 1 (default) or 0: with 1 the plan-driven recovery keeps the row estimates in registers
  *                 (needs r <= 6 with tiles of 2^14, r <= 12 with 2^13, any r with 2^12 or less); with 0
  *                 they go through a [r][d] scratch array

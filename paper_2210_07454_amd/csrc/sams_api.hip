@@ -9,7 +9,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 1};
+Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 1, 1};
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -188,6 +188,9 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "stage_interleave")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.stage_interleave = value;
+    } else if (!strcmp(key, "acc_wide")) {
+        if (value < 0 || value > 1) return SAMS_EINVAL;
+        g_tun.acc_wide = value;
     } else if (!strcmp(key, "sketch_path")) {
         if (value < 0 || value > 3) return SAMS_EINVAL;
         g_tun.sketch_path = value;

@@ -66,7 +66,7 @@ enum PlanMode { PLAN_ATOMIC = 0, PLAN_LDS_ROW = 1, PLAN_BINNED = 2 };
 // static permutation "coordinate order -> bucket order" of the binned path (see sams_plan.hip)
 struct Plan {
     int mode;
-    int win_log2, tile_log2, chunk_log2, acc_threads, run_pad, stage_rows, stage_ilv;
+    int win_log2, tile_log2, chunk_log2, acc_threads, run_pad, stage_rows, stage_ilv, acc_wide;
     int64_t nbins, ntile, dpad, rowlen;
     uint16_t *srcp;     // [r][rowlen]      slot -> coordinate inside its tile (bits 0-14) and sign (bit 15), or padding
     uint32_t *dst16;    // [r][rowlen/16]   stream position of each group of 16 slots
@@ -96,6 +96,7 @@ struct Tunables {
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats
     int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
     int stage_interleave; // 1 = the workers' staged copies are interleaved in pieces of 32 stream positions
+    int acc_wide;         // 1 = the accumulate kernel with 16-byte loads where its shape allows (1024 threads, 2048-position chunks)
 };
 extern Tunables g_tun;
 

@@ -739,6 +739,101 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     for (int t = threadIdx.x; t < lim; t += THREADS) out[t] = win[t];
 }
 
+// Variant with 16-byte loads (1024 threads, chunks of 2048 positions): the lower half of the workgroup streams
+// the values, the upper half the meta words, four consecutive positions per thread and load; they meet in the
+// LDS exchange buffers (values and meta words in arrays of their own), from which every thread then takes two
+// consecutive positions and works as in k_bin_accumulate.  Same order of additions, same results.
+__global__ void __launch_bounds__(1024)
+k_bin_accumulate_q(const float *__restrict__ stg, const uint32_t *__restrict__ meta,
+                   const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg,
+                   int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
+{
+    constexpr int CH = 2048;
+    extern __shared__ float lds[];
+    const int W = 1 << win_log2;
+    float *win = lds;
+    uint32_t *xv = reinterpret_cast<uint32_t *>(lds + W);            // [2][CH] value bits
+    uint32_t *xm = xv + 2 * CH;                                      // [2][CH] meta words
+    const int64_t id = blockIdx.x;
+    const int64_t slot = id / kNumXcd;
+    const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
+    const int32_t i = (int32_t)(slot % n);
+    if (group >= (int64_t)rg.rj * nbins) return;
+    const int32_t jj = (int32_t)(group / nbins), j = rg.j0 + jj;
+    const int64_t bin = group % nbins;
+    for (int t = threadIdx.x; t < W; t += 1024) win[t] = 0.f;
+    const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
+    const bool is_meta = threadIdx.x >= 512;                         // uniform over a wavefront
+    const uint32_t tt = threadIdx.x & 511u;
+    // this thread's stream: position b0 + x + 4 tt of the bin is at src[x * mul + off]
+    const uint32_t *src;
+    int64_t mul;
+    if (is_meta) {
+        src = meta + (int64_t)j * rowlen + b0 + 4 * tt;
+        mul = 1;
+    } else {
+        src = reinterpret_cast<const uint32_t *>(stg) + stage_row(rg, n, rowlen, i, jj) + stage_pos(rg, n, (uint32_t)b0) +
+              stage_pos(rg, n, 4 * tt);
+        mul = rg.ilv ? n : 1;
+    }
+    uint32_t *xmine = (is_meta ? xm : xv) + 4 * tt;
+    const int64_t nchunk = (b1 - b0) / CH;
+    const uint32_t wmask = (uint32_t)W - 1u;
+    typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
+    vec4u ring[kAccDepth];
+    auto fetch = [&](int64_t q) -> vec4u {
+        const vec4u *p = reinterpret_cast<const vec4u *>(src + q * CH * mul);
+        // plain loads for both halves: a streaming hint on the meta words would keep the n workers from sharing
+        // them through the L2 (measured: 5.3 instead of 4.6 ms), and the compiler folds the two halves' loads
+        // into one instruction, so the values cannot carry a hint of their own
+        return *p;
+    };
+    if (nchunk > 0) {                                                // uniform over the workgroup
+        const int64_t last = nchunk - 1;
+#pragma unroll
+        for (int s = 0; s < kAccDepth; ++s) {
+            ring[s] = fetch(s < last ? s : last);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (int64_t q0 = 0; q0 < nchunk; q0 += kAccDepth) {
+#pragma unroll
+            for (int s = 0; s < kAccDepth; ++s) {
+                const int64_t q = q0 + s;
+                if (q < nchunk) {                                    // uniform over the workgroup
+                    const int half = (int)(q & 1) * CH;
+                    *reinterpret_cast<vec4u *>(xmine + half) = ring[s];
+                    __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+                    const uint2 pv = *reinterpret_cast<const uint2 *>(xv + half + 2 * threadIdx.x);
+                    const uint2 pm = *reinterpret_cast<const uint2 *>(xm + half + 2 * threadIdx.x);
+                    const uint32_t vals[2] = {pv.x, pv.y}, words[2] = {pm.x, pm.y};
+#pragma unroll
+                    for (int z = 0; z < 2; ++z) {
+                        uint32_t word = words[z];
+                        if (!(word & kMetaNotFirst)) {
+                            const uint32_t w = word & wmask;
+                            float x = win[w] + __uint_as_float(vals[z]);
+                            while (word & kMetaHasNext) {
+                                const uint32_t at = (word >> kMetaNextShift) & (CH - 1);
+                                x = x + __uint_as_float(xv[half + at]);
+                                word = xm[half + at];
+                            }
+                            win[w] = x;
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                ring[s] = fetch((q + kAccDepth) < last ? (q + kAccDepth) : last);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    __syncthreads();
+    const int64_t base = bin << win_log2;
+    float *out = S + ((int64_t)i * rg.r + j) * c + base;
+    const int64_t lim = (c - base) < W ? (c - base) : W;
+    for (int t = threadIdx.x; t < lim; t += 1024) out[t] = win[t];
+}
+
 // ------------------------------------------------------------------------------------------
 // the plan run backwards, for the recovery of stage 3 (Sec. II-C: the row estimates s_j(l) S[j,h_j(l)])
 // ------------------------------------------------------------------------------------------
@@ -1058,6 +1153,20 @@ static int dispatch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_a
 {
     const Plan &pl = ctx->plan;
     const int un = (1 << pl.chunk_log2) / pl.acc_threads;
+    if (pl.acc_wide && pl.acc_threads == 1024 && un == 2) {
+        if (set_attr) {
+            SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate_q, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         kMaxLdsBytes));
+            return SAMS_OK;
+        }
+        const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)4 * 2048 * 4;
+        const int64_t groups = (int64_t)rg.rj * pl.nbins;
+        const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
+        ProfScope ps(ctx, KID_BIN_ACCUMULATE);
+        hipLaunchKernelGGL(k_bin_accumulate_q, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
+                           pl.meta, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
+        return SAMS_OK;
+    }
 #define SAMS_ACC(TH, UN) \
     if (pl.acc_threads == TH && un == UN) return launch_acc<TH, UN>(ctx, S_workers, rg, set_attr);
     SAMS_ACC(1024, 1) SAMS_ACC(1024, 2) SAMS_ACC(512, 1) SAMS_ACC(512, 2) SAMS_ACC(512, 4)
@@ -1099,6 +1208,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.acc_threads = tun.acc_threads ? tun.acc_threads : (pl.win_log2 >= 15 ? 1024 : 512);
     pl.run_pad = tun.run_pad;
     pl.stage_ilv = tun.stage_interleave ? 1 : 0;
+    pl.acc_wide = tun.acc_wide ? 1 : 0;
     pl.stage_rows = (tun.stage_rows <= 0 || tun.stage_rows > ctx->r) ? ctx->r : tun.stage_rows;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
