@@ -62,13 +62,20 @@ def kernel_algorithmic_bytes(name, d, n, r, c, k, pa=False):
 
 def load_traffic(kernel, workload):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary for this
-    kernel and workload has been recorded under profiles/."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
+    workload has been recorded under profiles/ (rows: kernel, launches, fetched raw, fetched scaled, written,
+    total scaled, in GB; a timing slot such as k_head_scatter covers the variants whose names start with it)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"step_{workload}_hbm_traffic.txt")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get(kernel)
+            for line in f:
+                cols = line.strip().split(",")
+                if line.startswith("#") or len(cols) < 6 or cols[0] == "kernel":
+                    continue
+                if cols[0].split("::")[-1].split("<")[0].startswith(kernel):
+                    return round(float(cols[-1]) * 1e9)
     except (OSError, ValueError):
-        return None
+        pass
+    return None
 
 
 def cpu_baseline(w, sample_d):
