@@ -78,3 +78,13 @@ def test_configure_rejects_unknown_keys_and_bad_values_without_a_gpu():
     assert lib.sams_profile_kernels() > 10
     names = {lib.sams_profile_name(q).decode() for q in range(lib.sams_profile_kernels())}
     assert {"k_head_scatter", "k_bin_accumulate", "k_sel_hist"} <= names
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box of this build has one GPU: bench.py says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], cwd=root, capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode != 0 and "ONE GPU" in p.stderr
