@@ -63,8 +63,10 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
                 const uint32_t *hash_host, void *hip_stream);
 
 /*
- * Process-wide tuning knobs, read by later sams_create calls (never changes results beyond the order of
- * fp32 additions inside a bucket).  Keys:
+ * Process-wide tuning knobs (never change results beyond the order of fp32 additions inside a bucket).
+ * sams_create copies the current set into the new context, and every later call on that context reads only that
+ * copy: changing a knob never affects a context that already exists.  sams_configure and the copy are serialised
+ * against each other, so they may be called from different threads.  Keys:
  *   "tile_log2"   0 or 6..14 (default 0): log2 of the coordinates per tile of the binned sketch path.  0 = chosen
  *                 from r, d, n: 2^14 (2^13 for r > 6, 2^12 for r > 12), or less (down to 2^8) while the first pass
  *                 would have too few workgroups to fill the chip (it has one per tile with "fuse_head" 1, one per
@@ -84,6 +86,10 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 the binned path) also writes the sorted copy of e_u that sketch_accumulate needs, and a
  *                 following sketch_accumulate called with that same e_u pointer skips its first pass.
  *                 The caller must then not write to e_u between the two calls (the algorithm never does).
+ *                 The sorted copy lives in the context's staging buffer and is forgotten as soon as anything else
+ *                 uses that buffer (unsketch_topk, unsketch_estimates, a sketch_accumulate that stages row groups)
+ *                 or e_u changes through this library (any amsgrad_ef_update*): a later sketch_accumulate of the
+ *                 same pointer then runs both passes again.
  *                 1: one workgroup per tile loops over the workers; 2: one workgroup per (tile, worker), the
  *                 workers of a tile sharing the plan's metadata through one L2, and the (1 - beta2) h^2 term of
  *                 v on I_{t-1} added by a small kernel of its own (same results bit for bit).
@@ -211,8 +217,8 @@ int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t 
                 float *delta);
 
 /*
- * Second round with over-selection (Sec. III-A: "select the largest Pk coordinates to extract their exact
- * values ... finally select the top-k coordinates among these Pk").  For a context created with k = P*k_out:
+ * Second round with over-selection (Sec. III-A): P*k candidates are taken by their estimates, their exact values
+ * are fetched, and the k largest of those are kept.  For a context created with k = P*k_out:
  * after unsketch_topk (P*k_out candidates) and gather_topk (their exact averaged values), keep the k_out
  * candidates with the largest |delta_in|, ties going to the smaller coordinate, in ascending coordinate order.
  *   idx_in   [k] int32 in, ascending (unsketch_topk's output)     delta_in  [k] in (gather_topk's output)

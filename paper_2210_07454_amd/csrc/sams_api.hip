@@ -2,6 +2,7 @@
 // optional per-kernel timing, and the calls into the per-stage enqueue functions.
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 
 #include "sams_ctx.h"
@@ -10,6 +11,7 @@ namespace sams {
 
 int g_last_hip_error = 0;
 Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 1, 1};
+static std::mutex g_tun_mutex;      // sams_configure against the copy sams_create takes
 
 static const char *const kKernelNames[KID_COUNT] = {
     "k_fill_u32", "k_hash_dump", "k_tail_x", "k_tail_zero_e", "k_head", "k_sketch_atomic", "k_reduce",
@@ -93,6 +95,10 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
     ctx->d = d; ctx->n = n; ctx->r = r; ctx->c = c; ctx->k = k;
     ctx->stream = (hipStream_t)hip_stream;
     ctx->prof_only = -1;
+    {
+        std::lock_guard<std::mutex> lock(g_tun_mutex);
+        ctx->tun = g_tun;                                            // every later call reads this copy only
+    }
     ctx->hp.r = r;
     ctx->hp.modc = make_modc((uint32_t)c);
     for (int j = 0; j < r; ++j) {
@@ -122,7 +128,7 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
         ctx->scratch_bytes += a.bytes;
     }
     int rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
-    if (rc == SAMS_OK && g_tun.sketch_path != 1) rc = plan_create(ctx, g_tun);
+    if (rc == SAMS_OK && ctx->tun.sketch_path != 1) rc = plan_create(ctx, ctx->tun);
     if (rc != SAMS_OK) {
         sams_destroy(ctx);
         return rc;
@@ -155,6 +161,7 @@ int sams_destroy(sams_ctx *ctx)
 int sams_configure(const char *key, int value)
 {
     if (!key) return SAMS_EINVAL;
+    std::lock_guard<std::mutex> lock(g_tun_mutex);
     if (!strcmp(key, "tile_log2")) {
         if (value != 0 && (value < 6 || value > 14)) return SAMS_EINVAL;
         g_tun.tile_log2 = value;
@@ -311,7 +318,7 @@ int unsketch_topk(sams_ctx *ctx, const float *S_mean, const float *vhat, int32_t
         !aligned16(est_sel))
         return SAMS_EINVAL;
     SAMS_TRY(enqueue_estimate(ctx, S_mean, vhat, ctx->est));
-    return enqueue_select(ctx, ctx->est, ctx->d, ctx->k, idx, est_sel);
+    return enqueue_select(ctx, ctx->stream, ctx_sel_scratch(ctx), ctx->est, ctx->d, ctx->k, idx, est_sel);
 }
 
 int topk_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_out, int32_t *idx_out,
@@ -319,7 +326,9 @@ int topk_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int
 {
     if (!ctx || !idx_in || !delta_in || !idx_out || !delta_out || k_out < 1 || k_out > ctx->k) return SAMS_EINVAL;
     if (!aligned16(idx_in) || !aligned16(delta_in) || !aligned16(idx_out) || !aligned16(delta_out)) return SAMS_EINVAL;
-    return enqueue_refine(ctx, idx_in, delta_in, ctx->k, k_out, idx_out, delta_out);
+    // the estimate scratch is free at this point: it holds the positions among the candidates
+    return enqueue_refine(ctx, ctx->stream, ctx_sel_scratch(ctx), reinterpret_cast<int32_t *>(ctx->est), idx_in, delta_in,
+                          ctx->k, k_out, idx_out, delta_out);
 }
 
 int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t *idx, float *U_workers,

@@ -82,7 +82,8 @@ struct Plan {
     bool fused_median;  // stage 3 keeps the row estimates in registers (decided when the plan is built)
 };
 
-// process-wide tunables read by sams_create (set through sams_configure)
+// tunables: sams_configure edits the process-wide set, sams_create copies it into the context, and every
+// later call on that context reads only its own copy
 struct Tunables {
     int tile_log2;     // coordinates per tile of the binned path (0 = chosen from d)
     int win_log2;      // buckets per LDS window
@@ -99,6 +100,15 @@ struct Tunables {
     int acc_wide;         // 1 = the accumulate kernel with 16-byte loads where its shape allows (1024 threads, 2048-position chunks)
 };
 extern Tunables g_tun;
+
+// scratch of one radix selection (enqueue_select): the context's, or the static one of topk_refine_static
+struct SelScratch {
+    uint32_t *hist;          // [kHistBins]
+    SelState *sel;           // [1]
+    uint32_t *cnt;           // [2][ntile_cap]  per-wavefront-tile counts: greater, equal
+    uint32_t *base;          // [2][ntile_cap]  exclusive prefix: selected before, equal before
+    int64_t ntile_cap;       // tiles of kSelTile keys the arrays have room for
+};
 
 }  // namespace sams
 
@@ -117,6 +127,7 @@ struct sams_ctx {
     int64_t ntile;
     int64_t scratch_bytes;
     sams::Plan plan;
+    sams::Tunables tun;      // the tunables as they were when the context was created
     // per-kernel timing (host)
     int prof_on;
     int prof_only;           // kernel id the timing is restricted to, -1 = every kernel
@@ -144,7 +155,7 @@ struct ProfScope {
     int slot;
     ProfScope(sams_ctx *c, int kid) : ctx(c), slot(-1)
     {
-        if (c->prof_on && (c->prof_only < 0 || c->prof_only == kid) && c->prof_used < kProfPool) {
+        if (c && c->prof_on && (c->prof_only < 0 || c->prof_only == kid) && c->prof_used < kProfPool) {
             slot = c->prof_used++;
             c->prof[slot].kid = kid;
             (void)hipEventRecord(c->prof[slot].a, c->stream);
@@ -161,6 +172,12 @@ struct ProfScope {
     do {                                                                                         \
         ::sams::ProfScope ps_((ctx), (kid));                                                     \
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, (ctx)->stream, __VA_ARGS__);      \
+    } while (0)
+// the same on a given stream, for code that also runs without a context (ctx may be null: no timing then)
+#define SAMS_LAUNCH_ON(ctx, stream, kid, kernel, grid, block, ...)                               \
+    do {                                                                                         \
+        ::sams::ProfScope ps_((ctx), (kid));                                                     \
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, (stream), __VA_ARGS__);           \
     } while (0)
 
 // median of R row estimates (Sec. II-C); for an even R the lower middle element
@@ -209,8 +226,11 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                          const int32_t *idx_prev, int64_t k_prev);       // I_{t-1}, as handed to the tail
 // sams_select.hip
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
-int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel);
-int enqueue_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_in, int64_t k_out,
-                   int32_t *idx_out, float *delta_out);
+// ctx may be null (no per-kernel timing); the work goes to `stream`, the scratch is the caller's
+int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, const float *keys, int64_t len, int64_t k,
+                   int32_t *idx, float *val_sel);
+int enqueue_refine(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int32_t *pos, const int32_t *idx_in,
+                   const float *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out, float *delta_out);
+SelScratch ctx_sel_scratch(const sams_ctx *ctx);
 
 }  // namespace sams

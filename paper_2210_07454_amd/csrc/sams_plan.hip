@@ -1037,6 +1037,7 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
     if (!pl.fused_median) return SAMS_OK;
     const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
     float *lk = pl.stg;
+    pl.staged_u = nullptr;                                           // the looked-up values overwrite any staged vector
     {
         ProfScope ps(ctx, KID_BIN_LOOKUP);
         const int32_t nsplit = lookup_split(pl, ctx->r);
@@ -1067,6 +1068,7 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
     Plan &pl = ctx->plan;
     const int64_t L = (int64_t)1 << pl.tile_log2, W = (int64_t)1 << pl.win_log2;
     float *lk = pl.stg;                                              // the staging buffer is idle between two sketches
+    pl.staged_u = nullptr;                                           // ... and whatever vector it held is overwritten
     const int64_t cap = (int64_t)ctx->n * pl.stage_rows;             // rows of looked-up values it can hold
     for (int32_t j0 = 0; j0 < ctx->r; j0 += (int32_t)cap) {
         const int32_t rj = (ctx->r - j0) < cap ? (ctx->r - j0) : (int32_t)cap;
@@ -1359,7 +1361,7 @@ void plan_destroy(sams_ctx *ctx)
 
 bool head_can_fuse(const sams_ctx *ctx)
 {
-    return g_tun.fuse_head && ctx->plan.mode == PLAN_BINNED && (ctx->d & 3) == 0 && ctx->plan.tile_log2 <= 14;
+    return ctx->tun.fuse_head && ctx->plan.mode == PLAN_BINNED && (ctx->d & 3) == 0 && ctx->plan.tile_log2 <= 14;
 }
 
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
@@ -1373,7 +1375,7 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
         ProfScope ps(ctx, KID_HEAD_SCATTER);
         const dim3 grid((unsigned)(per * kNumXcd));
         const RowGroup rg = {0, pl.stage_rows, pl.stage_rows, ctx->r, pl.stage_ilv};
-        if (g_tun.fuse_head == 2) {                                  // one workgroup per (tile, worker)
+        if (ctx->tun.fuse_head == 2) {                                  // one workgroup per (tile, worker)
             const dim3 wgrid((unsigned)(per * kNumXcd * ctx->n));
             if (pa)
                 hipLaunchKernelGGL(k_head_scatter_w<true>, wgrid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream,
@@ -1392,7 +1394,7 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
                                pl.rowlen);
     }
-    if (g_tun.fuse_head == 2 && !pa && k_prev > 0) {
+    if (ctx->tun.fuse_head == 2 && !pa && k_prev > 0) {
         if (ctx->n >= kWideMinWorkers)
             SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_wide, (unsigned)((k_prev + kWideCoords - 1) / kWideCoords),
                         256, g, idx_prev, k_prev, ctx->n, ctx->d, 1.0f - beta2, v, vhat);
@@ -1430,7 +1432,7 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
         const RowGroup rg = {j0, (ctx->r - j0) < pl.stage_rows ? (ctx->r - j0) : pl.stage_rows, pl.stage_rows, ctx->r, pl.stage_ilv};
         if (j0 > 0 || pl.staged_u != u) {                            // not staged by a fused head: pass 1 now
             ProfScope ps(ctx, KID_BIN_SCATTER);
-            hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd * ctx->n)), dim3((unsigned)g_tun.scatter_threads),
+            hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd * ctx->n)), dim3((unsigned)ctx->tun.scatter_threads),
                                (size_t)(L * 4), ctx->stream, u, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg,
                                ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);
         }

@@ -382,7 +382,7 @@ int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, floa
 {
     const int block = 256;
     const int grid = grid_for(ctx->d, block);
-    if (ctx->plan.mode == PLAN_BINNED && g_tun.estimate_path == 0) {
+    if (ctx->plan.mode == PLAN_BINNED && ctx->tun.estimate_path == 0) {
         bool done = false;
         SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done));
         if (done) return SAMS_OK;
@@ -429,39 +429,47 @@ k_refine_map(const int32_t *__restrict__ idx_in, const int32_t *__restrict__ pos
     if (q < k_out) idx_out[q] = idx_in[pos[q]];
 }
 
+SelScratch ctx_sel_scratch(const sams_ctx *ctx)
+{
+    return SelScratch{ctx->hist, ctx->sel, ctx->cnt, ctx->base, ctx->ntile};
+}
+
 // the k entries of keys[0..len) with the largest magnitude, ties to the smaller position; positions ascending
-int enqueue_select(sams_ctx *ctx, const float *keys, int64_t len, int64_t k, int32_t *idx, float *val_sel)
+int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, const float *keys, int64_t len, int64_t k,
+                   int32_t *idx, float *val_sel)
 {
     if (len <= kSelSmallMax) {
-        SAMS_LAUNCH(ctx, KID_SEL_SMALL, k_sel_small, 1, 1024, keys, len, (uint32_t)k, idx, val_sel);
+        SAMS_LAUNCH_ON(ctx, stream, KID_SEL_SMALL, k_sel_small, 1, 1024, keys, len, (uint32_t)k, idx, val_sel);
         SAMS_HIP(hipGetLastError());
         return SAMS_OK;
     }
-    const int64_t nt = (len + kSelTile - 1) / kSelTile;               // <= ctx->ntile since len <= d
-    uint32_t *cnt_gt = ctx->cnt, *cnt_eq = ctx->cnt + ctx->ntile;
-    uint32_t *sel_base = ctx->base, *eq_base = ctx->base + ctx->ntile;
-    SAMS_LAUNCH(ctx, KID_SEL_INIT, k_sel_init, 1, 256, ctx->sel, (uint32_t)k, ctx->hist);
+    const int64_t nt = (len + kSelTile - 1) / kSelTile;
+    if (nt > sc.ntile_cap) return SAMS_EINVAL;
+    uint32_t *cnt_gt = sc.cnt, *cnt_eq = sc.cnt + sc.ntile_cap;
+    uint32_t *sel_base = sc.base, *eq_base = sc.base + sc.ntile_cap;
+    SAMS_LAUNCH_ON(ctx, stream, KID_SEL_INIT, k_sel_init, 1, 256, sc.sel, (uint32_t)k, sc.hist);
     for (int pass = 0; pass < kSelPasses; ++pass) {
-        SAMS_LAUNCH(ctx, KID_SEL_HIST, k_sel_hist, grid_for(len, 256 * 16, 4096), 256, keys, len, pass,
-                    ctx->sel, ctx->hist);
-        SAMS_LAUNCH(ctx, KID_SEL_PICK, k_sel_pick, 1, 1024, ctx->sel, ctx->hist, pass);
+        SAMS_LAUNCH_ON(ctx, stream, KID_SEL_HIST, k_sel_hist, grid_for(len, 256 * 16, 4096), 256, keys, len, pass,
+                       sc.sel, sc.hist);
+        SAMS_LAUNCH_ON(ctx, stream, KID_SEL_PICK, k_sel_pick, 1, 1024, sc.sel, sc.hist, pass);
     }
     const int waves_per_block = 256 / kWave;
     const int tgrid = (int)((nt + waves_per_block - 1) / waves_per_block);
-    SAMS_LAUNCH(ctx, KID_SEL_COUNT, k_sel_count, tgrid, 256, keys, len, ctx->sel, cnt_gt, cnt_eq, nt);
-    SAMS_LAUNCH(ctx, KID_SEL_SCAN, k_sel_scan, 1, 1024, cnt_gt, cnt_eq, nt, ctx->sel, sel_base, eq_base);
-    SAMS_LAUNCH(ctx, KID_SEL_WRITE, k_sel_write, tgrid, 256, keys, len, ctx->sel, sel_base, eq_base, nt, k, idx,
-                val_sel);
+    SAMS_LAUNCH_ON(ctx, stream, KID_SEL_COUNT, k_sel_count, tgrid, 256, keys, len, sc.sel, cnt_gt, cnt_eq, nt);
+    SAMS_LAUNCH_ON(ctx, stream, KID_SEL_SCAN, k_sel_scan, 1, 1024, cnt_gt, cnt_eq, nt, sc.sel, sel_base, eq_base);
+    SAMS_LAUNCH_ON(ctx, stream, KID_SEL_WRITE, k_sel_write, tgrid, 256, keys, len, sc.sel, sel_base, eq_base, nt, k,
+                   idx, val_sel);
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
 }
 
-int enqueue_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_in, int64_t k_out,
-                   int32_t *idx_out, float *delta_out)
+// Second round with over-selection (Sec. III-A): the k_out candidates with the largest |delta_in|.  pos: k_out
+// int32 of scratch (positions among the candidates).
+int enqueue_refine(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int32_t *pos, const int32_t *idx_in,
+                   const float *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out, float *delta_out)
 {
-    int32_t *pos = reinterpret_cast<int32_t *>(ctx->est);             // the estimate scratch is free at this point
-    SAMS_TRY(enqueue_select(ctx, delta_in, k_in, k_out, pos, delta_out));
-    SAMS_LAUNCH(ctx, KID_REFINE_MAP, k_refine_map, grid_for(k_out, 256), 256, idx_in, pos, k_out, idx_out);
+    SAMS_TRY(enqueue_select(ctx, stream, sc, delta_in, k_in, k_out, pos, delta_out));
+    SAMS_LAUNCH_ON(ctx, stream, KID_REFINE_MAP, k_refine_map, grid_for(k_out, 256), 256, idx_in, pos, k_out, idx_out);
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;
 }

@@ -523,6 +523,96 @@ def test_exact_recovery_chain_is_bit_exact_end_to_end(sams):
         assert np.array_equal(host(b.e_u), st["e"])
 
 
+@pytest.mark.parametrize("fuse", [1, 2])
+def test_resketch_after_recovery_does_not_trust_a_stale_staged_copy(sams, fuse):
+    """A fused head leaves the sorted copy of e_u in the staging buffer and the next sketch_accumulate(e_u) uses it.
+    The recovery of stage 3 works through the same buffer, so a second sketch_accumulate of the same e_u after
+    unsketch_topk / unsketch_estimates must run both passes again: its tables equal the sequential sum bit for bit."""
+    d, n, r, c, k = 70_000, 3, 5, 9_001, 300
+    rng = np.random.default_rng(17)
+    hp = inputs.hash_params(r, seed=4)
+    o = Oracle("f32")
+    f = lambda *s: (rng.standard_normal(s) * 10.0 ** rng.uniform(-4, 0, s)).astype(np.float32)
+    g, m, e, x = f(n, d), f(n, d), f(n, d), f(d)
+    v = np.full(d, 1e-8, np.float32)
+    vhat = v.copy()
+    for key, val in dict(PATHS["default"], fuse_head=fuse, sketch_path=2, tile_log2=10, win_log2=9, chunk_log2=9,
+                         acc_threads=256).items():
+        sams.sams_configure(key, val)
+    try:
+        with sams.Context(d, n, r, c, k, hp) as ctx:
+            md, ed, vd, vhd, xd = dev(m), dev(e), dev(v), dev(vhat), dev(x)
+            ctx.amsgrad_ef_update(dev(g), md, ed, vd, vhd, xd, None, None, 0, 0.9, 0.99, 1e-3)
+            o.head(g, m, e, v, vhat, None, 0.9, 0.99)
+            want = np.stack([o.sketch(e[i], hp, c) for i in range(n)])
+            S = torch.empty((n, r, c), device="cuda")
+            Sm = torch.empty((r, c), device="cuda")
+            idx = torch.empty(k, device="cuda", dtype=torch.int32)
+            est = torch.empty(d, device="cuda")
+            ctx.sketch_accumulate(ed, S)                      # consumes the staged copy
+            assert np.array_equal(host(S), want)
+            ctx.sketch_reduce(S, Sm)
+            ctx.unsketch_topk(Sm, vhd, idx, None)             # the recovery overwrites the staging buffer
+            S.fill_(3.0)
+            ctx.sketch_accumulate(ed, S)
+            assert np.array_equal(host(S), want)
+            ctx.unsketch_estimates(Sm, vhd, est)
+            S.fill_(5.0)
+            ctx.sketch_accumulate(ed, S)
+            assert np.array_equal(host(S), want)
+    finally:
+        for key, val in PATHS["default"].items():
+            sams.sams_configure(key, val)
+
+
+def test_a_context_keeps_the_tunables_it_was_created_with(sams):
+    """sams_create copies the tunables; reconfiguring afterwards changes neither the kernels an existing context
+    launches (counted through the per-kernel timing) nor its results."""
+    d, n, r, c, k = 50_000, 3, 5, 5_000, 200
+    rng = np.random.default_rng(23)
+    hp = inputs.hash_params(r, seed=6)
+    f = lambda *s: (rng.standard_normal(s) * 10.0 ** rng.uniform(-4, 0, s)).astype(np.float32)
+    g, m, e, x = f(n, d), f(n, d), f(n, d), f(d)
+    v = np.full(d, 1e-8, np.float32)
+
+    def one_run(ctx):
+        md, ed, vd, vhd, xd = dev(m), dev(e), dev(v), dev(v.copy()), dev(x)
+        S = torch.empty((n, r, c), device="cuda")
+        Sm = torch.empty((r, c), device="cuda")
+        idx = torch.empty(k, device="cuda", dtype=torch.int32)
+        ctx.sams_profile_enable(True)
+        ctx.amsgrad_ef_update(dev(g), md, ed, vd, vhd, xd, None, None, 0, 0.9, 0.99, 1e-3)
+        ctx.sketch_accumulate(ed, S)
+        ctx.sketch_reduce(S, Sm)
+        ctx.unsketch_topk(Sm, vhd, idx, None)
+        ctx.sams_profile_enable(False)
+        launches = {kn: cnt for kn, (_, cnt) in ctx.sams_profile_read().items()}
+        return launches, host(S).copy(), host(idx).copy(), host(ed).copy()
+
+    first = dict(PATHS["default"], fuse_head=2, sketch_path=2, scatter_threads=512, estimate_path=0)
+    other = dict(PATHS["default"], fuse_head=0, sketch_path=1, scatter_threads=256, estimate_path=1, tile_log2=9,
+                 win_log2=8, chunk_log2=8, acc_threads=256)
+    try:
+        for key, val in first.items():
+            sams.sams_configure(key, val)
+        with sams.Context(d, n, r, c, k, hp) as ctx:
+            before = one_run(ctx)
+            assert before[0].get("k_head_scatter") == 1 and "k_head" not in before[0]
+            for key, val in other.items():
+                sams.sams_configure(key, val)
+            after = one_run(ctx)
+            assert after[0] == before[0]
+            assert all(np.array_equal(a, b) for a, b in zip(after[1:], before[1:]))
+            with sams.Context(d, n, r, c, k, hp) as ctx2:            # a new context does follow the new settings
+                fresh = one_run(ctx2)
+                assert fresh[0].get("k_head") == 1 and "k_head_scatter" not in fresh[0]
+                assert fresh[0].get("k_sketch_atomic") == 1 and fresh[0].get("k_estimate") == 1
+                assert np.array_equal(fresh[3], before[3])      # the head is exact on every path
+    finally:
+        for key, val in PATHS["default"].items():
+            sams.sams_configure(key, val)
+
+
 def test_invalid_arguments_are_rejected_without_launching(sams):
     hp = inputs.hash_params(5)
     bad = [dict(d=0), dict(k=0), dict(k=1001), dict(r=17), dict(c=0), dict(n=0), dict(d=inputs.P31)]
