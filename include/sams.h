@@ -39,6 +39,7 @@ extern "C" {
 #define SAMS_EHIP (-3)
 
 #define SAMS_MAX_ROWS 16
+#define SAMS_STATIC_MAX_CANDIDATES 8388608   /* largest k_in topk_refine_static accepts (2^23) */
 
 typedef struct sams_ctx sams_ctx;
 
@@ -228,6 +229,28 @@ int gather_topk(sams_ctx *ctx, const float *u, const float *vhat, const int32_t 
  */
 int topk_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_out, int32_t *idx_out,
                 float *delta_out);
+
+/*
+ * topk_refine for callers that cannot allocate device memory or create a context: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same selection, same kernels, same results as
+ * topk_refine(ctx, ...) with ctx->k = k_in, but context-free: the scratch of the selection (k_out positions, a radix
+ * histogram, per-tile counts and prefixes; about 4*SAMS_STATIC_MAX_CANDIDATES + 64 KiB bytes) is a static device
+ * array inside the library, which every GPU the library runs on holds until the process ends.  The call allocates
+ * and frees nothing and records no memset (every clear is a kernel).
+ *   idx_in   [k_in] int32 in, ascending     delta_in [k_in] in      1 <= k_out <= k_in <= SAMS_STATIC_MAX_CANDIDATES
+ *   idx_out  [k_out] int32 out              delta_out [k_out] out   (all device pointers of the current device, 16-byte aligned)
+ *   hip_stream  the hipStream_t (as void*) of the current device to enqueue on; NULL = the default stream
+ * Returns SAMS_EINVAL for a null or misaligned pointer or a size outside the range above (nothing enqueued),
+ * SAMS_EHIP for a runtime error.  The first call on a device looks up the array's address (hipGetSymbolAddress;
+ * sams_create does the same look-up, so a process that has created a context on the device has it already) and
+ * should be made outside stream capture.  All calls on one GPU share the one array, which keeps the previous call's
+ * contents: calls that overlap in time on the same GPU (different streams, or graphs replayed concurrently) race; calls
+ * ordered by a stream or by events do not.
+ * topk_refine_static_max_candidates() returns SAMS_STATIC_MAX_CANDIDATES as the library was built.
+ */
+int topk_refine_static(const int32_t *idx_in, const float *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out,
+                       float *delta_out, void *hip_stream);
+int64_t topk_refine_static_max_candidates(void);
 
 /*
  * Stage 5 -- AMSGrad update with error feedback (Alg. 2).  One call finishes iteration t and starts

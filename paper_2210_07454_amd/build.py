@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 SO = os.path.join(HERE, "libsams.so")
-SOURCES = ["sams_api.hip", "sams_update.hip", "sams_sketch.hip", "sams_plan.hip", "sams_select.hip"]
+SOURCES = ["sams_api.hip", "sams_update.hip", "sams_sketch.hip", "sams_plan.hip", "sams_select.hip", "sams_noalloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

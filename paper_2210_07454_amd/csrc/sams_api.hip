@@ -127,7 +127,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
         }
         ctx->scratch_bytes += a.bytes;
     }
-    int rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
+    void *static_scratch = nullptr;
+    int rc = static_scratch_ptr(&static_scratch);                    // resolved here so that topk_refine_static never has to
+    if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
     if (rc == SAMS_OK && ctx->tun.sketch_path != 1) rc = plan_create(ctx, ctx->tun);
     if (rc != SAMS_OK) {
         sams_destroy(ctx);

@@ -232,5 +232,7 @@ int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, cons
 int enqueue_refine(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int32_t *pos, const int32_t *idx_in,
                    const float *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out, float *delta_out);
 SelScratch ctx_sel_scratch(const sams_ctx *ctx);
+// sams_noalloc.hip: device address of the static scratch of topk_refine_static on the current device
+int static_scratch_ptr(void **out);
 
 }  // namespace sams

@@ -23,7 +23,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_precondition_device_memory", "sams_last_hip_error", "sams_hash_dump",
            "sams_configure", "sams_sketch_mode", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_only", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk", "topk_refine",
-           "amsgrad_ef_update", "amsgrad_ef_update_pa"]
+           "amsgrad_ef_update", "amsgrad_ef_update_pa", "topk_refine_static", "topk_refine_static_max_candidates"]
 
 _lib = None
 
@@ -70,8 +70,12 @@ def load() -> ctypes.CDLL:
     lib.topk_refine.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.amsgrad_ef_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
     lib.amsgrad_ef_update_pa.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32]
+    lib.topk_refine_static.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+    lib.topk_refine_static_max_candidates.argtypes = []
+    lib.topk_refine_static_max_candidates.restype = i64
     for name in EXPORTS:
-        if name not in ("sams_scratch_bytes", "sams_profile_name", "sams_precondition_device_memory"):
+        if name not in ("sams_scratch_bytes", "sams_profile_name", "sams_precondition_device_memory",
+                        "topk_refine_static_max_candidates"):
             getattr(lib, name).restype = ctypes.c_int
     lib.sams_profile_name.restype = ctypes.c_char_p
     _lib = lib
@@ -107,6 +111,18 @@ def _ptr(t, dtype=None, shape=None, name="tensor"):
 def _check(code, where):
     if code != SAMS_OK:
         raise SamsError(code, where)
+
+
+def topk_refine_static(idx_in, delta_in, k_out, idx_out, delta_out, stream=None):
+    """Context-free topk_refine on the library's static scratch (allocates nothing); see sams.h."""
+    if not torch.cuda.is_available():
+        raise RuntimeError("paper_2210_07454_amd needs a GPU: no CPU fallback exists")
+    k_in = idx_in.numel()
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load().topk_refine_static(
+        _ptr(idx_in, torch.int32, (k_in,), "idx_in"), _ptr(delta_in, torch.float32, (k_in,), "delta_in"), int(k_in),
+        int(k_out), _ptr(idx_out, torch.int32, (k_out,), "idx_out"), _ptr(delta_out, torch.float32, (k_out,), "delta_out"),
+        ctypes.c_void_p(st.cuda_stream)), "topk_refine_static")
 
 
 class Context:
