@@ -80,8 +80,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "acc_threads" 0, 256, 512 or 1024 (default 0 = 1024 for 2^15 windows, else 512): workgroup size of the binned accumulation; must not
  *                 exceed 2^chunk_log2, and a window plus two chunks of 8 bytes must fit in 160 KiB of LDS
  *                 (otherwise sams_create returns SAMS_EINVAL)
- *   "run_pad"     16 (default) or 32: stream positions a (tile, window) run is padded to, so that the
- *                 staging writes cover whole 64- or 128-byte pieces
+ *   "run_pad"     4, 8, 16 (default) or 32: stream positions a (tile, window) run is padded to, so that a run
+ *                 is written to the staging buffer as whole 16-, 32-, 64- or 128-byte pieces (less padding means
+ *                 fewer staged bytes, but runs that share a memory line with their neighbours)
  *   "scatter_threads" 256, 512 or 1024 (default 1024): workgroup size of the binned scatter pass
  *   "fuse_head"   0 (default), 1 or 2: with 1 or 2, amsgrad_ef_update or amsgrad_ef_update_pa (when it runs the head and the context uses
  *                 the binned path) also writes the sorted copy of e_u that sketch_accumulate needs, and a
@@ -101,8 +102,11 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 positions lie next to each other (one 128-byte line each), so that the workgroups of the workers,
  *                 which run side by side, write and read one region per (row, window) instead of n distant ones;
  *                 0: one contiguous copy per (worker, row).  Same results either way.
- *   "acc_wide"    1 (default) or 0: with 1024 threads and 2048-position chunks the binned accumulation reads its two
- *                 streams with 16-byte loads (half of the workgroup each) instead of 4-byte loads.  Same results.
+ *   "acc_wide"    2 (default), 1 or 0: with 1024 threads and 2048-position chunks the binned accumulation reads its
+ *                 streams with 16-byte loads instead of 4-byte loads (1, 2), and with 2 the per-position metadata
+ *                 (4 bytes) is replaced by per-chunk records (2-byte codes plus a short list of the positions that
+ *                 share a bucket inside the chunk: 2.5 bytes per position).  A context whose hashes put more than
+ *                 256 such positions into one chunk (small or badly filled windows) falls back to 1.  Same results.
  *   "fuse_median" 1 (default) or 0: with 1 the plan-driven recovery keeps the row estimates in registers
  *                 (needs r <= 6 with tiles of 2^14, r <= 12 with 2^13, any r with 2^12 or less); with 0
  *                 they go through a [r][d] scratch array
@@ -123,6 +127,11 @@ int sams_destroy(sams_ctx *ctx);
 /* How this context carries out sketch_accumulate: 0 = one global atomic add per term, 1 = row by row in LDS
  * (c fits one window), 2 = the binned, order-preserving path.  -1 for a NULL context. */
 int sams_sketch_mode(const sams_ctx *ctx);
+
+/* Which kernel carries out the second pass of the binned path for this context: 0 = 4-byte loads, 1 = 16-byte loads
+ * of values and per-position meta words, 2 = 16-byte loads of values and compact chunk records (see "acc_wide").
+ * -1 when the context does not use the binned path (or is NULL). */
+int sams_accumulate_variant(const sams_ctx *ctx);
 
 /* Device bytes the context allocated. */
 int64_t sams_scratch_bytes(const sams_ctx *ctx);

@@ -10,7 +10,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 1, 1};
+Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 1, 2};
 static std::mutex g_tun_mutex;      // sams_configure against the copy sams_create takes
 
 static const char *const kKernelNames[KID_COUNT] = {
@@ -192,13 +192,13 @@ int sams_configure(const char *key, int value)
         if (value < 0 || value > SAMS_MAX_ROWS) return SAMS_EINVAL;
         g_tun.stage_rows = value;
     } else if (!strcmp(key, "run_pad")) {
-        if (value != 16 && value != 32) return SAMS_EINVAL;
+        if (value != 4 && value != 8 && value != 16 && value != 32) return SAMS_EINVAL;
         g_tun.run_pad = value;
     } else if (!strcmp(key, "stage_interleave")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.stage_interleave = value;
     } else if (!strcmp(key, "acc_wide")) {
-        if (value < 0 || value > 1) return SAMS_EINVAL;
+        if (value < 0 || value > 2) return SAMS_EINVAL;
         g_tun.acc_wide = value;
     } else if (!strcmp(key, "sketch_path")) {
         if (value < 0 || value > 3) return SAMS_EINVAL;
@@ -210,6 +210,11 @@ int sams_configure(const char *key, int value)
 }
 
 int sams_sketch_mode(const sams_ctx *ctx) { return ctx ? ctx->plan.mode : -1; }
+
+int sams_accumulate_variant(const sams_ctx *ctx)
+{
+    return (ctx && ctx->plan.mode == PLAN_BINNED) ? ctx->plan.acc_variant : -1;
+}
 
 int64_t sams_scratch_bytes(const sams_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }
 
@@ -311,7 +316,7 @@ int unsketch_estimates(sams_ctx *ctx, const float *S_mean, const float *vhat, fl
 {
     if (!ctx || !S_mean || !est || !aligned16(S_mean) || !aligned16(est) || !aligned16(vhat))
         return SAMS_EINVAL;
-    return enqueue_estimate(ctx, S_mean, vhat, est);
+    return enqueue_estimate(ctx, S_mean, vhat, est, nullptr, nullptr);
 }
 
 int unsketch_topk(sams_ctx *ctx, const float *S_mean, const float *vhat, int32_t *idx, float *est_sel)
@@ -319,8 +324,13 @@ int unsketch_topk(sams_ctx *ctx, const float *S_mean, const float *vhat, int32_t
     if (!ctx || !S_mean || !idx || !aligned16(S_mean) || !aligned16(idx) || !aligned16(vhat) ||
         !aligned16(est_sel))
         return SAMS_EINVAL;
-    SAMS_TRY(enqueue_estimate(ctx, S_mean, vhat, ctx->est));
-    return enqueue_select(ctx, ctx->stream, ctx_sel_scratch(ctx), ctx->est, ctx->d, ctx->k, idx, est_sel);
+    // the selection's state is reset first, so that the estimate kernel can already take the first histogram
+    const SelScratch sc = ctx_sel_scratch(ctx);
+    const bool passes = select_uses_passes(ctx->d);
+    bool hist0_done = false;
+    if (passes) SAMS_TRY(enqueue_select_begin(ctx, ctx->stream, sc, ctx->k));
+    SAMS_TRY(enqueue_estimate(ctx, S_mean, vhat, ctx->est, passes ? sc.hist : nullptr, &hist0_done));
+    return enqueue_select(ctx, ctx->stream, sc, ctx->est, ctx->d, ctx->k, idx, est_sel, passes, hist0_done);
 }
 
 int topk_refine(sams_ctx *ctx, const int32_t *idx_in, const float *delta_in, int64_t k_out, int32_t *idx_out,

@@ -66,13 +66,15 @@ enum PlanMode { PLAN_ATOMIC = 0, PLAN_LDS_ROW = 1, PLAN_BINNED = 2 };
 // static permutation "coordinate order -> bucket order" of the binned path (see sams_plan.hip)
 struct Plan {
     int mode;
-    int win_log2, tile_log2, chunk_log2, acc_threads, run_pad, stage_rows, stage_ilv, acc_wide;
+    int acc_variant;    // pass 2: 0 = 4-byte loads, 1 = 16-byte loads of values and meta words, 2 = 16-byte loads of values and chunk records
+    int win_log2, tile_log2, chunk_log2, acc_threads, run_pad, grp_log2, stage_rows, stage_ilv, acc_wide;
     int64_t nbins, ntile, dpad, rowlen;
     uint16_t *srcp;     // [r][rowlen]      slot -> coordinate inside its tile (bits 0-14) and sign (bit 15), or padding
-    uint32_t *dst16;    // [r][rowlen/16]   stream position of each group of 16 slots
+    uint32_t *dst16;    // [r][rowlen >> grp_log2]  stream position of each group of 2^grp_log2 slots (16, or the run padding if smaller)
     uint32_t *pbase;    // [r][ntile+1]     first slot of each tile
     uint32_t *binbase;  // [r][nbins+1]     start of each bin in the row stream (multiples of the chunk)
-    uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags
+    uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags (absent with acc_variant 2)
+    uint32_t *rec;      // [r][rowlen/4096][2560] chunk records of acc_variant 2: 4096 16-bit codes, 512 chain entries
     uint16_t *wlow;     // [r][rowlen]          per stream position: bucket in window only (what the recovery reads)
     float *stg;         // n * stage_rows * rowlen floats: per-step staging, signed values at their stream positions
                         //                      ([stage_rows][rowlen/32][n][32], or [n][stage_rows][rowlen] without stage_ilv)
@@ -95,9 +97,10 @@ struct Tunables {
     int fuse_head;        // 1, 2 = amsgrad_ef_update also stages u for the next sketch_accumulate (2: a workgroup per worker)
     int fuse_median;      // 1 = recovery keeps the row estimates in registers where the shape allows, 0 = through memory
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats
-    int run_pad;          // runs are padded to a multiple of this many stream positions (16 or 32)
+    int run_pad;          // runs are padded to a multiple of this many stream positions (4, 8, 16 or 32)
     int stage_interleave; // 1 = the workers' staged copies are interleaved in pieces of 32 stream positions
-    int acc_wide;         // 1 = the accumulate kernel with 16-byte loads where its shape allows (1024 threads, 2048-position chunks)
+    int acc_wide;         // accumulate kernel where its shape allows (1024 threads, 2048-position chunks): 1 = 16-byte loads,
+                          // 2 = 16-byte loads and compact chunk records instead of meta words (falls back to 1 when a chunk has too many chains)
 };
 extern Tunables g_tun;
 
@@ -198,6 +201,23 @@ __device__ __forceinline__ float median_of(float (&a)[R])
     return a[(R - 1) / 2];
 }
 
+// exclusive prefix sum over the 1024 threads of a block (part: 1024 words of LDS)
+__device__ __forceinline__ uint32_t block_exclusive_scan_1024(uint32_t val, uint32_t *part)
+{
+    const int t = threadIdx.x;
+    part[t] = val;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        const uint32_t x = t >= off ? part[t - off] : 0u;
+        __syncthreads();
+        part[t] += x;
+        __syncthreads();
+    }
+    const uint32_t excl = part[t] - val;
+    __syncthreads();
+    return excl;
+}
+
 // ---- enqueue functions (all asynchronous on ctx->stream; return SAMS_OK or SAMS_EHIP) ----
 int enqueue_fill_u32(sams_ctx *ctx, uint32_t *p, int64_t n, uint32_t val);
 int enqueue_hash_dump(sams_ctx *ctx, int32_t *bucket, int8_t *sign);
@@ -219,16 +239,19 @@ void plan_destroy(sams_ctx *ctx);
 int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers);
 int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *rowest);
 // whole recovery through the plan when the fused collect+median kernel applies; *done says whether it ran
-int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done);
+int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done,
+                                    uint32_t *hist);   // hist: null, or where to add the first-digit histogram of |est|
 bool head_can_fuse(const sams_ctx *ctx);
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
                          float beta1, float beta2, float rho, bool pa,   // pa: v, vhat are [n][d] (Alg. 1)
                          const int32_t *idx_prev, int64_t k_prev);       // I_{t-1}, as handed to the tail
 // sams_select.hip
-int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est);
+int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, uint32_t *hist, bool *hist_done);
+bool select_uses_passes(int64_t len);
+int enqueue_select_begin(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int64_t k);
 // ctx may be null (no per-kernel timing); the work goes to `stream`, the scratch is the caller's
 int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, const float *keys, int64_t len, int64_t k,
-                   int32_t *idx, float *val_sel);
+                   int32_t *idx, float *val_sel, bool begun, bool hist0_done);
 int enqueue_refine(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int32_t *pos, const int32_t *idx_in,
                    const float *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out, float *delta_out);
 SelScratch ctx_sel_scratch(const sams_ctx *ctx);

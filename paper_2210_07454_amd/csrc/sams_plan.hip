@@ -9,10 +9,11 @@
 //     W = 2^win_log2 buckets that fit in LDS;
 //   * every row owns a "stream": bin after bin, and inside a bin tile after tile, the coordinates that
 //     fall into that bin in ascending order.  The piece of one (tile, bin) is a "run"; runs are padded
-//     to 16 elements (one 64-byte sector) and bins to a whole number of chunks;
+//     to a multiple of the run padding (4, 8, 16 or 32 elements) and bins to a whole number of chunks;
 //   * seen from a tile, its padded runs laid one after the other are its "slots": srcp[row][slot]
 //     names the coordinate (and its sign) a slot takes its value from (or marks padding), and
-//     dst16[row][slot / 16] says where in the row stream that group of 16 slots goes;
+//     dst16[row][slot / G] says where in the row stream that group of G slots goes (G = the run padding,
+//     at most 16);
 //   * meta[row][pos] describes stream position pos: the bucket inside the window, and -- per chunk of
 //     CH consecutive positions -- a chain linking the positions that hit the same bucket.
 // Per step, pass 1 (k_bin_scatter) streams each worker's vector through LDS once and writes, for every
@@ -31,7 +32,6 @@
 namespace sams {
 
 constexpr int kPlanThreads = 1024;
-constexpr int kScatterThreads = 256;
 constexpr int kNumXcd = 8;
 constexpr int kScatterBatch = 4;             // groups of 4 slots whose metadata a scatter thread loads ahead
 constexpr int kAccDepth = 8;                // chunks in flight per workgroup of the accumulate kernel
@@ -39,12 +39,27 @@ constexpr int kFusedThreads = 1024;          // kernels whose threads own the sa
 constexpr int kFusedIters = 4;              // tiles of at most 2^14 coordinates = 4 float4 per thread
 constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one compute unit; the dynamic-LDS cap of every kernel here
 constexpr int64_t kOrderedSingleBinMaxD = (int64_t)1 << 22;     // largest d sketched in order when c fits one window
-constexpr int kRunPad = 16;                 // slot-group granularity in elements (64 bytes); runs are padded to a multiple of it
 
 constexpr uint16_t kSrcPad = 0x7fffu;          // slot source meaning "padding": tiles hold at most 2^14 coordinates
 constexpr uint32_t kMetaNextShift = 15;
 constexpr uint32_t kMetaHasNext = 1u << 26;
 constexpr uint32_t kMetaNotFirst = 1u << 27;   // padding, or a position some earlier position adds
+constexpr uint32_t kMetaPad = 1u << 28;        // padding (always together with kMetaNotFirst)
+// Chunk records: the compact form of the meta words that k_bin_accumulate_r reads, one record per 4096 stream
+// positions.  A record is 4096 16-bit codes followed by kRecChains chain entries.  Within a chunk, a position whose
+// bucket no other position shares has its bucket as code (< 0x8000); the positions that share a bucket form a
+// chain and carry 0x8000 | rank, the ranks of a chain being consecutive in stream order; padding carries
+// 0x8000 | (a rank in the dummy range above kRecRanks).  Entry e describes chain e: bucket (bits 0-14), rank of its
+// first position (bits 15-24), number of positions (bits 25-31; 0 = unused entry).
+constexpr int kRecChunk = 4096;
+constexpr int kRecCodeWords = kRecChunk / 2;
+constexpr int kRecChains = 512;                // chains a chunk may have
+constexpr int kRecRanks = 1024;                // chain positions a chunk may have
+constexpr int kRecPadRanks = 256;              // dummy ranks of the padding positions
+constexpr int kRecMaxChain = 127;              // positions one chain may have
+constexpr int kRecWords = kRecCodeWords + kRecChains;
+constexpr uint32_t kCodeChain = 0x8000u, kCodeRankMask = 0x7ffu;
+constexpr int kRecDepth = 4;                   // chunks in flight per workgroup of k_bin_accumulate_r (even)
 
 // streaming accesses: data touched once per step should not push the shared metadata out of L2.
 // One 16-byte nontemporal instruction each (the pointers are 16-byte aligned, as float4 requires).
@@ -78,6 +93,13 @@ __device__ __forceinline__ int64_t stage_row(const RowGroup &rg, int32_t n, int6
 __device__ __forceinline__ int64_t stage_pos(const RowGroup &rg, int32_t n, uint32_t p)
 {
     return rg.ilv ? ((int64_t)(p >> kIlvLog2) * n << kIlvLog2) + (p & ((1u << kIlvLog2) - 1u)) : (int64_t)p;
+}
+
+typedef uint32_t vec2u __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 load_stream2(const uint2 *p)
+{
+    const vec2u t = __builtin_nontemporal_load(reinterpret_cast<const vec2u *>(p));
+    return make_uint2(t.x, t.y);
 }
 
 __host__ __device__ __forceinline__ int pad_run(int len, int pad) { return (len + pad - 1) & ~(pad - 1); }
@@ -202,11 +224,11 @@ k_plan_tilelen(const uint16_t *__restrict__ bst, int pad, int64_t nbins, int64_t
 }
 
 // ------------------------------------------------------------------------------------------
-// plan step 3b: per (row, tile): the source of every slot, the stream position of every group of 16
+// plan step 3b: per (row, tile): the source of every slot, the stream position of every group of G
 // slots, and the bucket of every stream position
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_plan_place(HashParams hp, int pad, int tile_log2, int win_log2, int64_t nbins, int64_t ntile, int64_t dpad,
+k_plan_place(HashParams hp, int pad, int gl, int tile_log2, int win_log2, int64_t nbins, int64_t ntile, int64_t dpad,
              int64_t rowlen, const uint16_t *__restrict__ src, const uint16_t *__restrict__ bst,
              const uint32_t *__restrict__ off, const uint32_t *__restrict__ binbase,
              const uint32_t *__restrict__ pbase, uint16_t *__restrict__ srcp, uint32_t *__restrict__ dst16,
@@ -254,7 +276,7 @@ k_plan_place(HashParams hp, int pad, int tile_log2, int win_log2, int64_t nbins,
                 wlow[(int64_t)j * rowlen + start + s] = (uint16_t)wl;
             }
             srcp[(int64_t)j * rowlen + po + s] = sv;
-            if ((s & (kRunPad - 1)) == 0) dst16[((int64_t)j * rowlen + po + s) / kRunPad] = start + (uint32_t)s;
+            if ((s & ((1 << gl) - 1)) == 0) dst16[((int64_t)j * rowlen + po + s) >> gl] = start + (uint32_t)s;
         }
     }
 }
@@ -303,18 +325,105 @@ k_plan_chain(int chunk_log2, int64_t rowlen, uint32_t *__restrict__ meta)
 }
 
 // ------------------------------------------------------------------------------------------
+// plan step 4' (instead of step 4 where it applies): the chunk records of k_bin_accumulate_r
+// ------------------------------------------------------------------------------------------
+// One workgroup per (row, chunk of 4096 positions): sorts the chunk's positions by (bucket, position), finds the
+// groups that share a bucket and writes the record.  `over` is set when a chunk does not fit the record format
+// (too many chains or chain positions, or too long a chain): the caller then keeps the meta words.
+__global__ void __launch_bounds__(kPlanThreads)
+k_plan_records(const uint32_t *__restrict__ meta, uint32_t *__restrict__ rec, int64_t rowlen, uint32_t *__restrict__ over)
+{
+    __shared__ uint32_t keys[kRecChunk];
+    __shared__ uint32_t part[1024];
+    __shared__ uint32_t nchains;
+    const int t = threadIdx.x;
+    const int64_t nchunk = rowlen / kRecChunk;
+    const uint32_t *m = meta + (int64_t)blockIdx.y * rowlen + (int64_t)blockIdx.x * kRecChunk;
+    uint32_t *rc = rec + ((int64_t)blockIdx.y * nchunk + blockIdx.x) * kRecWords;
+    uint16_t *codes = reinterpret_cast<uint16_t *>(rc);
+    for (int p = t; p < kRecChunk; p += kPlanThreads) {
+        const uint32_t w = m[p];
+        const bool pad = (w & kMetaPad) != 0;
+        keys[p] = pad ? 0xffffffffu : (((w & 0x7fffu) << 12) | (uint32_t)p);
+        if (pad) codes[p] = (uint16_t)(kCodeChain | (uint32_t)kRecRanks | ((uint32_t)p & (kRecPadRanks - 1)));
+    }
+    __syncthreads();
+    for (int k = 2; k <= kRecChunk; k <<= 1) {
+        for (int jj = k >> 1; jj > 0; jj >>= 1) {
+            for (int q = t; q < kRecChunk; q += kPlanThreads) {
+                const int other = q ^ jj;
+                if (other > q) {
+                    const uint32_t a = keys[q], b = keys[other];
+                    const bool up = (q & k) == 0;
+                    if ((a > b) == up) {
+                        keys[q] = b;
+                        keys[other] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // thread t looks at the sorted elements 4t .. 4t+3
+    bool inchain[4], cstart[4];
+    uint32_t n_in = 0, n_cs = 0;
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        const int s0 = 4 * t + z;
+        const uint32_t key = keys[s0];
+        const bool valid = key != 0xffffffffu;
+        const uint32_t b = key >> 12;
+        const bool prev_same = valid && s0 > 0 && (keys[s0 - 1] >> 12) == b;
+        const bool next_same = valid && s0 + 1 < kRecChunk && keys[s0 + 1] != 0xffffffffu && (keys[s0 + 1] >> 12) == b;
+        inchain[z] = prev_same || next_same;
+        cstart[z] = !prev_same && next_same;
+        n_in += inchain[z] ? 1u : 0u;
+        n_cs += cstart[z] ? 1u : 0u;
+    }
+    uint32_t rank = block_exclusive_scan_1024(n_in, part);
+    uint32_t e = block_exclusive_scan_1024(n_cs, part);
+    bool too_long = false;
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        const int s0 = 4 * t + z;
+        const uint32_t key = keys[s0];
+        if (key == 0xffffffffu) continue;
+        const uint32_t b = key >> 12, pos = key & 0xfffu;
+        codes[pos] = (uint16_t)(inchain[z] ? (kCodeChain | (rank & kCodeRankMask)) : b);
+        if (cstart[z]) {
+            uint32_t len = 1;
+            while (s0 + (int)len < kRecChunk && keys[s0 + len] != 0xffffffffu && (keys[s0 + len] >> 12) == b &&
+                   len <= (uint32_t)kRecMaxChain)
+                ++len;
+            if (len > (uint32_t)kRecMaxChain) too_long = true;
+            if (e < (uint32_t)kRecChains && rank < (uint32_t)kRecRanks)
+                rc[kRecCodeWords + e] = b | (rank << 15) | ((len & 127u) << 25);
+            ++e;
+        }
+        if (inchain[z]) ++rank;
+    }
+    if (t == kPlanThreads - 1) {
+        nchains = e;
+        if (e > (uint32_t)kRecChains || rank > (uint32_t)kRecRanks) atomicOr(over, 1u);
+    }
+    if (too_long) atomicOr(over, 1u);
+    __syncthreads();
+    for (uint32_t q = nchains + (uint32_t)t; q < (uint32_t)kRecChains; q += kPlanThreads) rc[kRecCodeWords + q] = 0u;   // unused entries
+}
+
+// ------------------------------------------------------------------------------------------
 // pass 1: per tile, every worker's values to their positions in the row streams
 // ------------------------------------------------------------------------------------------
 // One workgroup per (tile, worker).  Workgroup ids are dealt round-robin to the 8 XCDs; consecutive tiles are
 // given to the same XCD so that neighbouring runs of a bin are written through one L2, and the n workers of
 // a tile sit there in consecutive slots so that the tile's plan metadata crosses the fabric once and comes
 // from that L2 for the other workers.  A thread owns 4 consecutive slots (always inside
-// one group of 16, hence one run): one 8-byte load of their sources, one 4-byte load of the group's
+// one group of G >= 4 slots, hence one run): one 8-byte load of their sources, one 4-byte load of the group's
 // stream position, 4 LDS reads and one 16-byte store -- nothing depends on another global load.
 __global__ void __launch_bounds__(1024)
 k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
               const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
-              int tile_log2, int64_t ntile, int64_t rowlen)
+              int tile_log2, int64_t ntile, int64_t rowlen, int gl)
 {
     extern __shared__ float tilebuf[];
     const int L = 1 << tile_log2;
@@ -340,10 +449,10 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
         for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
             const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
-            const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+            const uint32_t *dj = dst16 + (int64_t)j * (rowlen >> gl);
             float *oj = stg + stage_row(rg, n, rowlen, i, j - rg.j0);
             // four groups of 4 slots per thread and batch: their sources and positions are loaded unconditionally
-            // (clamped addresses; o1 - o0 is a multiple of 16, at least 16) before the first is used
+            // (clamped addresses; o1 - o0 is a multiple of 4, at least 4) before the first is used
             for (uint32_t ob = o0 + threadIdx.x * 4; ob < o1; ob += blockDim.x * 4 * kScatterBatch) {
                 uint2 packed4[kScatterBatch];
                 int64_t at4[kScatterBatch];
@@ -351,7 +460,7 @@ k_bin_scatter(const float *__restrict__ u, const uint16_t *__restrict__ srcp, co
                 for (int uu = 0; uu < kScatterBatch; ++uu) {
                     const uint32_t o = ob + (uint32_t)uu * blockDim.x * 4, oc = o < o1 ? o : o1 - 4;
                     packed4[uu] = *reinterpret_cast<const uint2 *>(sj + oc);
-                    at4[uu] = stage_pos(rg, n, dj[oc / kRunPad]) + (oc & (kRunPad - 1));
+                    at4[uu] = stage_pos(rg, n, dj[oc >> gl]) + (oc & ((1u << gl) - 1u));
                 }
 #pragma unroll
                 for (int uu = 0; uu < kScatterBatch; ++uu) {
@@ -389,7 +498,7 @@ template <bool PA>
 __global__ void __launch_bounds__(kFusedThreads)
 k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
                const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
-               int tile_log2, int64_t ntile, int64_t rowlen)
+               int tile_log2, int64_t ntile, int64_t rowlen, int gl)
 {
     extern __shared__ float tilebuf[];
     const int L = 1 << tile_log2;
@@ -455,11 +564,11 @@ k_head_scatter(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *_
         for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
             const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
-            const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+            const uint32_t *dj = dst16 + (int64_t)j * (rowlen >> gl);
             float *oj = stg + stage_row(rg, n, rowlen, i, j - rg.j0);
             for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
                 const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-                const int64_t at = stage_pos(rg, n, dj[o / kRunPad]) + (o & (kRunPad - 1));
+                const int64_t at = stage_pos(rg, n, dj[o >> gl]) + (o & ((1u << gl) - 1u));
                 const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
                                s3 = packed.y >> 16;
                 float4 v;
@@ -507,7 +616,7 @@ template <bool PA>
 __global__ void __launch_bounds__(kFusedThreads)
 k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
                  const uint32_t *__restrict__ pbase, float *__restrict__ stg, int32_t n, RowGroup rg, int64_t d,
-                 int tile_log2, int64_t ntile, int64_t rowlen)
+                 int tile_log2, int64_t ntile, int64_t rowlen, int gl)
 {
     extern __shared__ float tilebuf[];
     const int L = 1 << tile_log2;
@@ -578,11 +687,11 @@ k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t 
     for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
         const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
         const uint16_t *sj = srcp + (int64_t)j * rowlen;
-        const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+        const uint32_t *dj = dst16 + (int64_t)j * (rowlen >> gl);
         float *oj = stg + stage_row(rg, n, rowlen, i, j - rg.j0);
         for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
             const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-            const int64_t at = stage_pos(rg, n, dj[o / kRunPad]) + (o & (kRunPad - 1));
+            const int64_t at = stage_pos(rg, n, dj[o >> gl]) + (o & ((1u << gl) - 1u));
             const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu, s3 = packed.y >> 16;
             float4 v;
             v.x = (s0 == kSrcPad) ? 0.f : tilebuf[s0 & 0x7fffu]; v.x = (s0 & 0x8000u) ? -v.x : v.x;
@@ -834,6 +943,123 @@ k_bin_accumulate_q(const float *__restrict__ stg, const uint32_t *__restrict__ m
     for (int t = threadIdx.x; t < lim; t += 1024) out[t] = win[t];
 }
 
+// Variant reading chunk records instead of meta words (1024 threads, chunks of 4096 positions, windows of up to 2^15
+// buckets).  A thread owns four consecutive positions per chunk and keeps their values and codes in registers: one
+// 16-byte streaming load of the values, one 8-byte load of the codes (the records are shared by the n workers of a
+// (row, bin) through the L2); waves 0-1 also fetch the chunk's chain entries.  Per chunk: the positions that share
+// their bucket with another position of the chunk (about an eighth with 2^15 windows) put their values into a small
+// LDS array at their rank; after the one barrier every other position adds its value to its bucket, a plain
+// read-modify-write since nothing else touches that bucket before the next barrier, and thread e < 512 adds the
+// values of chain e to the chain's bucket in rank order, which is stream order.  The buckets of the chains and of
+// the single positions are disjoint, so the two need no barrier between them.  Same order of additions per bucket,
+// hence the same results, as k_bin_accumulate.
+typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
+
+// The chunk loop, instantiated per role of a wave (ENT: fetches chain entries; CHAINS: its threads process chains).
+// Separate copies of the loop rather than loads and stores under per-wave conditions: every load is then issued
+// unconditionally and in a fixed order, so that the compiler can wait for exactly the oldest one of the ring.
+template <bool ENT, bool CHAINS>
+__device__ __forceinline__ void acc_r_chunks(const vec4f *__restrict__ vsrc, int64_t vstride, const uint2 *__restrict__ csrc,
+                                             const vec4u *__restrict__ esrc, float *win, float *mv, uint32_t *ent,
+                                             int64_t nchunk)
+{
+    constexpr int kMv = kRecRanks + kRecPadRanks;
+    vec4f rv[kRecDepth];
+    uint2 rc[kRecDepth];
+    vec4u re[kRecDepth];
+    const int64_t last = nchunk - 1;
+#pragma unroll
+    for (int s = 0; s < kRecDepth; ++s) {
+        const int64_t qs = s < last ? s : last;
+        rv[s] = __builtin_nontemporal_load(vsrc + qs * vstride);
+        rc[s] = csrc[qs * (kRecWords / 2)];
+        if constexpr (ENT) re[s] = esrc[qs * (kRecWords / 4)];
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    for (int64_t q0 = 0; q0 < nchunk; q0 += kRecDepth) {
+#pragma unroll
+        for (int s = 0; s < kRecDepth; ++s) {
+            const int64_t q = q0 + s;
+            if (q < nchunk) {                                        // uniform over the workgroup
+                float *mvp = mv + (s & 1) * kMv;                      // q0 is even: the chunk's parity is that of s
+                uint32_t *entp = ent + (s & 1) * kRecChains;
+                const float vals[4] = {rv[s].x, rv[s].y, rv[s].z, rv[s].w};
+                const uint32_t codes[4] = {rc[s].x & 0xffffu, rc[s].x >> 16, rc[s].y & 0xffffu, rc[s].y >> 16};
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (codes[z] >= kCodeChain) mvp[codes[z] & kCodeRankMask] = vals[z];
+                if constexpr (ENT) *reinterpret_cast<vec4u *>(entp + 4 * threadIdx.x) = re[s];
+                __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+                    if (codes[z] < kCodeChain) win[codes[z]] = win[codes[z]] + vals[z];
+                if constexpr (CHAINS) {
+                    const uint32_t word = entp[threadIdx.x];
+                    const uint32_t cnt = word >> 25;
+                    if (cnt) {
+                        const uint32_t w = word & 0x7fffu;
+                        const float *mc = mvp + ((word >> 15) & (uint32_t)(kRecRanks - 1));
+                        float x = win[w];
+                        for (uint32_t o = 0; o < cnt; ++o) x = x + mc[o];
+                        win[w] = x;
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int64_t qn = (q + kRecDepth) < last ? (q + kRecDepth) : last;
+            rv[s] = __builtin_nontemporal_load(vsrc + qn * vstride);
+            rc[s] = csrc[qn * (kRecWords / 2)];
+            if constexpr (ENT) re[s] = esrc[qn * (kRecWords / 4)];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(1024)
+k_bin_accumulate_r(const float *__restrict__ stg, const uint32_t *__restrict__ rec,
+                   const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg,
+                   int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
+{
+    constexpr int CH = kRecChunk;
+    extern __shared__ float lds[];
+    const int W = 1 << win_log2;
+    float *win = lds;
+    float *mv = lds + W;                                             // [2][kRecRanks + kRecPadRanks] values of chain positions
+    uint32_t *ent = reinterpret_cast<uint32_t *>(mv + 2 * (kRecRanks + kRecPadRanks));   // [2][kRecChains]
+    const int64_t id = blockIdx.x;
+    const int64_t slot = id / kNumXcd;
+    const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
+    const int32_t i = (int32_t)(slot % n);
+    if (group >= (int64_t)rg.rj * nbins) return;
+    const int32_t jj = (int32_t)(group / nbins), j = rg.j0 + jj;
+    const int64_t bin = group % nbins;
+    const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
+    const int64_t nchunk = (b1 - b0) / CH;                           // bins are whole chunks (see plan_create)
+    for (int t = threadIdx.x; t < W; t += 1024) win[t] = 0.f;
+    if (nchunk > 0) {                                                // uniform over the workgroup
+        const uint32_t t = threadIdx.x;
+        // this thread's four positions of chunk q: values at vsrc[q * vstride], codes at csrc[q * (kRecWords / 2)]
+        const vec4f *vsrc = reinterpret_cast<const vec4f *>(stg + stage_row(rg, n, rowlen, i, jj) +
+                                                            stage_pos(rg, n, (uint32_t)b0) + stage_pos(rg, n, 4 * t));
+        const int64_t vstride = (int64_t)(CH / 4) * (rg.ilv ? n : 1);
+        const uint32_t *r0 = rec + ((int64_t)j * (rowlen / CH) + b0 / CH) * kRecWords;
+        const uint2 *csrc = reinterpret_cast<const uint2 *>(r0) + t;
+        const vec4u *esrc = reinterpret_cast<const vec4u *>(r0 + kRecCodeWords) + (t & (kRecChains / 4 - 1));
+        const int wave = __builtin_amdgcn_readfirstlane((int)(t >> 6));   // uniform, kept in a scalar register
+        if (wave < kRecChains / 4 / kWave)
+            acc_r_chunks<true, true>(vsrc, vstride, csrc, esrc, win, mv, ent, nchunk);
+        else if (wave < kRecChains / kWave)
+            acc_r_chunks<false, true>(vsrc, vstride, csrc, esrc, win, mv, ent, nchunk);
+        else
+            acc_r_chunks<false, false>(vsrc, vstride, csrc, esrc, win, mv, ent, nchunk);
+    }
+    __syncthreads();
+    const int64_t base = bin << win_log2;
+    float *out = S + ((int64_t)i * rg.r + j) * c + base;
+    const int64_t lim = (c - base) < W ? (c - base) : W;
+    for (int t = threadIdx.x; t < lim; t += 1024) out[t] = win[t];
+}
+
 // ------------------------------------------------------------------------------------------
 // the plan run backwards, for the recovery of stage 3 (Sec. II-C: the row estimates s_j(l) S[j,h_j(l)])
 // ------------------------------------------------------------------------------------------
@@ -866,7 +1092,7 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint16_t *__restrict__ wlow
     const int64_t piece = (n4 + nsplit - 1) / nsplit;
     const int64_t q1 = (part + 1) * piece < n4 ? (part + 1) * piece : n4;
     for (int64_t q = part * piece + threadIdx.x; q < q1; q += blockDim.x) {
-        const uint2 w = m4[q];
+        const uint2 w = load_stream2(m4 + q);
         store_stream(o4 + q, make_float4(win[w.x & 0xffffu], win[w.x >> 16], win[w.y & 0xffffu], win[w.y >> 16]));
     }
 }
@@ -874,7 +1100,7 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint16_t *__restrict__ wlow
 __global__ void __launch_bounds__(1024)
 k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, const uint32_t *__restrict__ dst16,
               const uint32_t *__restrict__ pbase, float *__restrict__ rowest, int32_t j0, int32_t rj, int64_t d,
-              int tile_log2, int64_t ntile, int64_t rowlen)
+              int tile_log2, int64_t ntile, int64_t rowlen, int gl)
 {
     extern __shared__ float rowbuf[];                                // [2][L]
     const int L = 1 << tile_log2;
@@ -885,11 +1111,11 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
         float *buf = rowbuf + (j & 1) * L;
         const uint32_t o0 = pbase[(int64_t)j * (ntile + 1) + tile], o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
         const uint16_t *sj = srcp + (int64_t)j * rowlen;
-        const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+        const uint32_t *dj = dst16 + (int64_t)j * (rowlen >> gl);
         const float *lj = lk + (int64_t)(j - j0) * rowlen;
         for (uint32_t o = o0 + threadIdx.x * 4; o < o1; o += blockDim.x * 4) {
             const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-            const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+            const uint32_t at = dj[o >> gl] + (o & ((1u << gl) - 1u));
             const float4 v = load_stream(reinterpret_cast<const float4 *>(lj + at));
             const uint32_t s0 = packed.x & 0xffffu, s1 = packed.x >> 16, s2 = packed.y & 0xffffu,
                            s3 = packed.y >> 16;
@@ -919,9 +1145,9 @@ __global__ void __launch_bounds__(kFusedThreads)
 k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ srcp,
                      const uint32_t *__restrict__ dst16, const uint32_t *__restrict__ pbase,
                      const float *__restrict__ vhat, float *__restrict__ est, int64_t d, int tile_log2,
-                     int64_t ntile, int64_t rowlen)
+                     int64_t ntile, int64_t rowlen, int gl, uint32_t *__restrict__ hist)
 {
-    extern __shared__ float rowbuf[];                                // [2][L]
+    extern __shared__ float rowbuf[];                                // [2][L], at least kHistBins words in all
     const int L = 1 << tile_log2;
     const int64_t tile = blockIdx.x;
     const int64_t l0 = tile << tile_log2;
@@ -936,14 +1162,14 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
         o0 = pbase[(int64_t)j * (ntile + 1) + tile];
         o1 = pbase[(int64_t)j * (ntile + 1) + tile + 1];
         const uint16_t *sj = srcp + (int64_t)j * rowlen;
-        const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+        const uint32_t *dj = dst16 + (int64_t)j * (rowlen >> gl);
         const float *lj = lk + (int64_t)j * rowlen;
 #pragma unroll
         for (int s = 0; s < kCollectAhead; ++s) {
             const uint32_t o = o0 + (uint32_t)(s * kFusedThreads + (int)threadIdx.x) * 4u;
-            const uint32_t oc = o < o1 ? o : o1 - 4u;                // a tile has at least one group of 16 slots
-            pk[s] = *reinterpret_cast<const uint2 *>(sj + oc);
-            pv[s] = load_stream(reinterpret_cast<const float4 *>(lj + dj[oc / kRunPad] + (oc & (kRunPad - 1))));
+            const uint32_t oc = o < o1 ? o : o1 - 4u;                // a tile has at least one group of 4 slots
+            pk[s] = load_stream2(reinterpret_cast<const uint2 *>(sj + oc));
+            pv[s] = load_stream(reinterpret_cast<const float4 *>(lj + dj[oc >> gl] + (oc & ((1u << gl) - 1u))));
         }
     };
     auto place = [&](float *buf, const uint2 packed, const float4 v) {
@@ -963,12 +1189,12 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
             if (b0 + (uint32_t)(s * kFusedThreads + (int)threadIdx.x) * 4u < b1) place(buf, pk[s], pv[s]);
         {
             const uint16_t *sj = srcp + (int64_t)j * rowlen;
-            const uint32_t *dj = dst16 + (int64_t)j * (rowlen / kRunPad);
+            const uint32_t *dj = dst16 + (int64_t)j * (rowlen >> gl);
             const float *lj = lk + (int64_t)j * rowlen;
             for (uint32_t o = b0 + (uint32_t)(kCollectAhead * kFusedThreads + (int)threadIdx.x) * 4u; o < b1;
                  o += kFusedThreads * 4) {
-                const uint2 packed = *reinterpret_cast<const uint2 *>(sj + o);
-                const uint32_t at = dj[o / kRunPad] + (o & (kRunPad - 1));
+                const uint2 packed = load_stream2(reinterpret_cast<const uint2 *>(sj + o));
+                const uint32_t at = dj[o >> gl] + (o & ((1u << gl) - 1u));
                 place(buf, packed, load_stream(reinterpret_cast<const float4 *>(lj + at)));
             }
         }
@@ -981,6 +1207,15 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
             if (p < L) q = *reinterpret_cast<const float4 *>(buf + p);
             a[j][it][0] = q.x; a[j][it][1] = q.y; a[j][it][2] = q.z; a[j][it][3] = q.w;
         }
+    }
+    // hist != null: the selection follows, and the histogram of the first radix digit of |est| (its top 11 bits)
+    // is taken here, from the registers, instead of by a pass over the estimates of its own.  The row buffers are
+    // free by now (every thread has copied its part of the last row) and hold the workgroup's histogram.
+    uint32_t *lh = reinterpret_cast<uint32_t *>(rowbuf);
+    if (hist) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < kHistBins; b += kFusedThreads) lh[b] = 0;
+        __syncthreads();
     }
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
@@ -999,9 +1234,15 @@ k_bin_collect_median(const float *__restrict__ lk, const uint16_t *__restrict__ 
                 for (int j = 0; j < R; ++j) col[j] = a[j][it][t];
                 const float med = median_of<R>(col);
                 o[t] = vhat ? (med / sqrtf(vh[t])) : med;
+                if (hist) atomicAdd(&lh[(__float_as_uint(o[t]) & 0x7fffffffu) >> 20], 1u);
             }
             *reinterpret_cast<float4 *>(est + l0 + p) = make_float4(o[0], o[1], o[2], o[3]);
         }
+    }
+    if (hist) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < kHistBins; b += kFusedThreads)
+            if (lh[b]) atomicAdd(&hist[b], lh[b]);
     }
 }
 
@@ -1030,7 +1271,8 @@ static int32_t lookup_split(const Plan &pl, int32_t rows)
     return (int32_t)(nsplit < 1 ? 1 : (nsplit > 64 ? 64 : nsplit));
 }
 
-int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done)
+int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done,
+                                    uint32_t *hist)
 {
     Plan &pl = ctx->plan;
     *done = false;
@@ -1047,11 +1289,12 @@ int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const fl
     }
     {
         ProfScope ps(ctx, KID_BIN_COLLECT);
+        const size_t lds = (size_t)(2 * L * 4) > (size_t)kHistBins * 4 ? (size_t)(2 * L * 4) : (size_t)kHistBins * 4;
 #define SAMS_CM(RR, IT)                                                                                   \
     case RR:                                                                                              \
         hipLaunchKernelGGL((k_bin_collect_median<RR, IT>), dim3((unsigned)pl.ntile), dim3(kFusedThreads), \
-                           (size_t)(2 * L * 4), ctx->stream, lk, pl.srcp, pl.dst16, pl.pbase, vhat, est,   \
-                           ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);                                     \
+                           lds, ctx->stream, lk, pl.srcp, pl.dst16, pl.pbase, vhat, est,                   \
+                           ctx->d, pl.tile_log2, pl.ntile, pl.rowlen, pl.grp_log2, hist);                 \
         break;
         switch (ctx->r) {
             SAMS_FUSED_MEDIAN_VARIANTS(SAMS_CM)
@@ -1083,7 +1326,7 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
             ProfScope ps(ctx, KID_BIN_COLLECT);
             hipLaunchKernelGGL(k_bin_collect, dim3((unsigned)pl.ntile), dim3(1024), (size_t)(2 * L * 4),
                                ctx->stream, lk, pl.srcp, pl.dst16, pl.pbase, rowest, j0, rj, ctx->d, pl.tile_log2,
-                               pl.ntile, pl.rowlen);
+                               pl.ntile, pl.rowlen, pl.grp_log2);
         }
     }
     SAMS_HIP(hipGetLastError());
@@ -1155,18 +1398,23 @@ static int dispatch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_a
 {
     const Plan &pl = ctx->plan;
     const int un = (1 << pl.chunk_log2) / pl.acc_threads;
-    if (pl.acc_wide && pl.acc_threads == 1024 && un == 2) {
-        if (set_attr) {
-            SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate_q, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         kMaxLdsBytes));
-            return SAMS_OK;
-        }
-        const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)4 * 2048 * 4;
+    if (set_attr) {
+        SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate_q, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+        SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate_r, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+    }
+    if (!set_attr && pl.acc_variant >= 1) {
         const int64_t groups = (int64_t)rg.rj * pl.nbins;
         const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
         ProfScope ps(ctx, KID_BIN_ACCUMULATE);
-        hipLaunchKernelGGL(k_bin_accumulate_q, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
-                           pl.meta, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
+        if (pl.acc_variant == 2) {
+            const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * (kRecRanks + kRecPadRanks) * 4 + (size_t)2 * kRecChains * 4;
+            hipLaunchKernelGGL(k_bin_accumulate_r, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
+                               pl.rec, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
+        } else {
+            const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)4 * 2048 * 4;
+            hipLaunchKernelGGL(k_bin_accumulate_q, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
+                               pl.meta, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
+        }
         return SAMS_OK;
     }
 #define SAMS_ACC(TH, UN) \
@@ -1209,8 +1457,9 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
     pl.chunk_log2 = tun.chunk_log2 ? tun.chunk_log2 : (pl.win_log2 >= 15 ? 11 : 10);
     pl.acc_threads = tun.acc_threads ? tun.acc_threads : (pl.win_log2 >= 15 ? 1024 : 512);
     pl.run_pad = tun.run_pad;
+    pl.grp_log2 = tun.run_pad >= 16 ? 4 : (tun.run_pad == 8 ? 3 : 2);   // slot groups: the run padding, at most 16 slots
     pl.stage_ilv = tun.stage_interleave ? 1 : 0;
-    pl.acc_wide = tun.acc_wide ? 1 : 0;
+    pl.acc_wide = tun.acc_wide;
     pl.stage_rows = (tun.stage_rows <= 0 || tun.stage_rows > ctx->r) ? ctx->r : tun.stage_rows;
     const int64_t W = (int64_t)1 << pl.win_log2, L = (int64_t)1 << pl.tile_log2, CH = (int64_t)1 << pl.chunk_log2;
     pl.nbins = (ctx->c + W - 1) / W;
@@ -1282,13 +1531,17 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
             e = hipMemcpyAsync(h_tile, tilelen, (size_t)(r * pl.ntile * 4), hipMemcpyDeviceToHost, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
         if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        // bins are padded to whole chunks of the accumulate kernel that will read them: 4096 positions where the
+        // chunk-record kernel may run (its shape: 1024 threads, nominal chunks of 2048), else the chunk itself
+        const bool wide_shape = pl.acc_threads == 1024 && CH == 2048;
+        const int64_t BP = (wide_shape && pl.acc_wide >= 2) ? (int64_t)kRecChunk : CH;
         int64_t rowlen = 0;
         bool overflow = false;
         for (int64_t j = 0; j < r; ++j) {
             int64_t run = 0;
             for (int64_t b = 0; b < NB; ++b) {
                 h_base[j * (NB + 1) + b] = (uint32_t)run;
-                run += ((int64_t)h_total[j * NB + b] + CH - 1) / CH * CH;
+                run += ((int64_t)h_total[j * NB + b] + BP - 1) / BP * BP;
             }
             h_base[j * (NB + 1) + NB] = (uint32_t)run;
             if (run >= ((int64_t)1 << 32)) overflow = true;
@@ -1308,36 +1561,75 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         }
         if (rc != SAMS_OK) break;
         rc = dev_alloc(ctx, (void **)&pl.srcp, r * rowlen * 2);
-        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen / kRunPad) * 4);
+        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.dst16, r * (rowlen >> pl.grp_log2) * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.meta, r * rowlen * 4);
         if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.wlow, r * rowlen * 2);
-        if (rc == SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, n * pl.stage_rows * rowlen * 4);
+        if (rc != SAMS_OK) break;
+        e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(pl.pbase, h_tile, (size_t)(r * (pl.ntile + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        rc = enqueue_fill_u32(ctx, pl.meta, r * rowlen, kMetaNotFirst | kMetaPad);
+        if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, reinterpret_cast<uint32_t *>(pl.wlow), r * rowlen / 2, 0u);   // padding: bucket 0
+        if (rc != SAMS_OK) break;
+        {
+            ProfScope ps(ctx, KID_PLAN_BUILD);
+            hipLaunchKernelGGL(k_plan_place, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256),
+                               (size_t)((NB + 1) * 4), ctx->stream, ctx->hp, pl.run_pad, pl.grp_log2, pl.tile_log2, pl.win_log2, NB,
+                               pl.ntile, pl.dpad, rowlen, src, bst, off, pl.binbase, pl.pbase, pl.srcp, pl.dst16,
+                               pl.meta, pl.wlow);
+        }
+        e = hipStreamSynchronize(ctx->stream);                       // h_base and off are released below
+        if (e == hipSuccess) e = hipGetLastError();
+        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        // the build-time arrays are no longer needed: release them before anything else is allocated
+        for (int q = 0; q < 5; ++q)
+            if (*tmp[q]) { (void)hipFree(*tmp[q]); *tmp[q] = nullptr; }
+        // which accumulate kernel: the generic one, the one with 16-byte loads, or the one reading chunk records
+        pl.acc_variant = (wide_shape && pl.acc_wide >= 1) ? 1 : 0;
+        if (wide_shape && pl.acc_wide >= 2) {
+            uint32_t *over = nullptr, h_over = 0;
+            if (hipMalloc((void **)&over, 4) != hipSuccess) { (void)hipGetLastError(); rc = SAMS_ENOMEM; break; }
+            rc = dev_alloc(ctx, (void **)&pl.rec, r * (rowlen / kRecChunk) * kRecWords * 4);
+            if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, over, 1, 0u);
+            if (rc == SAMS_OK) {
+                ProfScope ps(ctx, KID_PLAN_BUILD);
+                hipLaunchKernelGGL(k_plan_records, dim3((unsigned)(rowlen / kRecChunk), (unsigned)r), dim3(kPlanThreads), 0,
+                                   ctx->stream, pl.meta, pl.rec, rowlen, over);
+                e = hipMemcpyAsync(&h_over, over, 4, hipMemcpyDeviceToHost, ctx->stream);
+                if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+                if (e == hipSuccess) e = hipGetLastError();
+                if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; }
+            }
+            (void)hipFree(over);
+            if (rc != SAMS_OK) break;
+            if (!h_over) {                                           // every chunk fits the record format: the meta words can go
+                pl.acc_variant = 2;
+                (void)hipFree(pl.meta);
+                pl.meta = nullptr;
+                ctx->scratch_bytes -= r * rowlen * 4;
+            } else {
+                (void)hipFree(pl.rec);
+                pl.rec = nullptr;
+                ctx->scratch_bytes -= r * (rowlen / kRecChunk) * kRecWords * 4;
+            }
+        }
+        if (pl.acc_variant != 2) {                                   // the kernels that read meta words need the chains
+            ProfScope ps(ctx, KID_PLAN_BUILD);
+            hipLaunchKernelGGL(k_plan_chain, dim3((unsigned)(rowlen / CH), (unsigned)r),
+                               dim3(CH < kPlanThreads ? (unsigned)CH : kPlanThreads), (size_t)(CH * 4), ctx->stream,
+                               pl.chunk_log2, rowlen, pl.meta);
+            e = hipStreamSynchronize(ctx->stream);
+            if (e == hipSuccess) e = hipGetLastError();
+            if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
+        }
+        rc = dev_alloc(ctx, (void **)&pl.stg, n * pl.stage_rows * rowlen * 4);
         // the median is fused when a thread can hold the row estimates of its coordinates and the staging
         // buffer can hold the looked-up values of all r rows; otherwise they go through rowest
         pl.fused_median = tun.fuse_median && fused_median_iters(ctx->r, pl.tile_log2) > 0 && (ctx->d & 3) == 0 &&
                           n * pl.stage_rows >= r;
         if (rc == SAMS_OK && !pl.fused_median) rc = dev_alloc(ctx, (void **)&pl.rowest, r * ctx->d * 4);
         if (rc != SAMS_OK) break;
-        e = hipMemcpyAsync(pl.binbase, h_base, (size_t)(r * (NB + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(pl.pbase, h_tile, (size_t)(r * (pl.ntile + 1) * 4), hipMemcpyHostToDevice, ctx->stream);
-        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
-        rc = enqueue_fill_u32(ctx, pl.meta, r * rowlen, kMetaNotFirst);
-        if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, reinterpret_cast<uint32_t *>(pl.wlow), r * rowlen / 2, 0u);   // padding: bucket 0
-        if (rc != SAMS_OK) break;
-        {
-            ProfScope ps(ctx, KID_PLAN_BUILD);
-            hipLaunchKernelGGL(k_plan_place, dim3((unsigned)pl.ntile, (unsigned)r), dim3(256),
-                               (size_t)((NB + 1) * 4), ctx->stream, ctx->hp, pl.run_pad, pl.tile_log2, pl.win_log2, NB,
-                               pl.ntile, pl.dpad, rowlen, src, bst, off, pl.binbase, pl.pbase, pl.srcp, pl.dst16,
-                               pl.meta, pl.wlow);
-            hipLaunchKernelGGL(k_plan_chain, dim3((unsigned)(rowlen / CH), (unsigned)r),
-                               dim3(CH < kPlanThreads ? (unsigned)CH : kPlanThreads), (size_t)(CH * 4), ctx->stream,
-                               pl.chunk_log2, rowlen, pl.meta);
-        }
-        e = hipStreamSynchronize(ctx->stream);                       // h_base and off are released below
-        if (e == hipSuccess) e = hipGetLastError();
-        if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
     } while (0);
     free(h_total);
     free(h_base);
@@ -1350,11 +1642,11 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
 void plan_destroy(sams_ctx *ctx)
 {
     Plan &pl = ctx->plan;
-    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.wlow, pl.stg, pl.rowest};
+    void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.rec, pl.wlow, pl.stg, pl.rowest};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     pl.srcp = nullptr;
-    pl.dst16 = pl.pbase = pl.binbase = pl.meta = nullptr;
+    pl.dst16 = pl.pbase = pl.binbase = pl.meta = pl.rec = nullptr;
     pl.wlow = nullptr;
     pl.stg = pl.rowest = nullptr;
 }
@@ -1380,19 +1672,19 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
             if (pa)
                 hipLaunchKernelGGL(k_head_scatter_w<true>, wgrid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream,
                                    ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2,
-                                   pl.ntile, pl.rowlen);
+                                   pl.ntile, pl.rowlen, pl.grp_log2);
             else
                 hipLaunchKernelGGL(k_head_scatter_w<false>, wgrid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream,
                                    ha, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2,
-                                   pl.ntile, pl.rowlen);
+                                   pl.ntile, pl.rowlen, pl.grp_log2);
         } else if (pa)
             hipLaunchKernelGGL(k_head_scatter<true>, grid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream, ha,
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
-                               pl.rowlen);
+                               pl.rowlen, pl.grp_log2);
         else
             hipLaunchKernelGGL(k_head_scatter<false>, grid, dim3(kFusedThreads), (size_t)(L * 4), ctx->stream, ha,
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
-                               pl.rowlen);
+                               pl.rowlen, pl.grp_log2);
     }
     if (ctx->tun.fuse_head == 2 && !pa && k_prev > 0) {
         if (ctx->n >= kWideMinWorkers)
@@ -1434,7 +1726,7 @@ int enqueue_sketch_planned(sams_ctx *ctx, const float *u, float *S_workers)
             ProfScope ps(ctx, KID_BIN_SCATTER);
             hipLaunchKernelGGL(k_bin_scatter, dim3((unsigned)(per * kNumXcd * ctx->n)), dim3((unsigned)ctx->tun.scatter_threads),
                                (size_t)(L * 4), ctx->stream, u, pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg,
-                               ctx->d, pl.tile_log2, pl.ntile, pl.rowlen);
+                               ctx->d, pl.tile_log2, pl.ntile, pl.rowlen, pl.grp_log2);
         }
         SAMS_HIP(hipGetLastError());
         SAMS_TRY(dispatch_acc(ctx, S_workers, rg, false));

@@ -75,7 +75,8 @@ __device__ __forceinline__ Keys4 load_keys4(const float *__restrict__ keys, int6
 {
     Keys4 q;
     if (l + 3 < len) {
-        const float4 t = *reinterpret_cast<const float4 *>(keys + l);
+        typedef float vec4f __attribute__((ext_vector_type(4)));
+        const vec4f t = __builtin_nontemporal_load(reinterpret_cast<const vec4f *>(keys + l));   // streamed: read once per pass
         q.v[0] = t.x; q.v[1] = t.y; q.v[2] = t.z; q.v[3] = t.w;
         q.have = 0xfu;
     } else {
@@ -127,23 +128,6 @@ k_sel_hist(const float *__restrict__ est, int64_t d, int pass, const SelState *_
     __syncthreads();
     for (int t = threadIdx.x; t < kHistBins; t += blockDim.x)
         if (lh[t]) atomicAdd(&hist[t], lh[t]);
-}
-
-// exclusive prefix sum over the 1024 threads of a block (part: 1024 words of LDS)
-__device__ __forceinline__ uint32_t block_exclusive_scan_1024(uint32_t val, uint32_t *part)
-{
-    const int t = threadIdx.x;
-    part[t] = val;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-        const uint32_t x = t >= off ? part[t - off] : 0u;
-        __syncthreads();
-        part[t] += x;
-        __syncthreads();
-    }
-    const uint32_t excl = part[t] - val;
-    __syncthreads();
-    return excl;
 }
 
 // choose the digit in which the k_rem-th largest key lies; clear the histogram for the next pass.
@@ -378,14 +362,20 @@ k_sel_small(const float *__restrict__ keys, int64_t len, uint32_t k, int32_t *__
                      val_sel);
 }
 
-int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est)
+// hist != null: the caller is about to select over est and has reset the selection state (enqueue_select_begin);
+// *hist_done tells whether the estimate kernel also took the histogram of the first radix digit
+int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, uint32_t *hist, bool *hist_done)
 {
+    if (hist_done) *hist_done = false;
     const int block = 256;
     const int grid = grid_for(ctx->d, block);
     if (ctx->plan.mode == PLAN_BINNED && ctx->tun.estimate_path == 0) {
         bool done = false;
-        SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done));
-        if (done) return SAMS_OK;
+        SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done, hist));
+        if (done) {
+            if (hist_done) *hist_done = hist != nullptr;
+            return SAMS_OK;
+        }
         SAMS_TRY(enqueue_row_estimates_planned(ctx, S_mean, ctx->plan.rowest));
         switch (ctx->r) {
 #define SAMS_CASE(R)                                                                                  \
@@ -434,9 +424,22 @@ SelScratch ctx_sel_scratch(const sams_ctx *ctx)
     return SelScratch{ctx->hist, ctx->sel, ctx->cnt, ctx->base, ctx->ntile};
 }
 
-// the k entries of keys[0..len) with the largest magnitude, ties to the smaller position; positions ascending
+// resets the selection state and the histogram for a selection of k out of len keys; nothing to do for the
+// one-workgroup selection of short vectors (returns false)
+bool select_uses_passes(int64_t len) { return len > kSelSmallMax; }
+
+int enqueue_select_begin(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int64_t k)
+{
+    SAMS_LAUNCH_ON(ctx, stream, KID_SEL_INIT, k_sel_init, 1, 256, sc.sel, (uint32_t)k, sc.hist);
+    SAMS_HIP(hipGetLastError());
+    return SAMS_OK;
+}
+
+// the k entries of keys[0..len) with the largest magnitude, ties to the smaller position; positions ascending.
+// begun: enqueue_select_begin has been called for this selection (otherwise it is called here);
+// hist0_done: the histogram of the first digit has been accumulated into sc.hist since then
 int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, const float *keys, int64_t len, int64_t k,
-                   int32_t *idx, float *val_sel)
+                   int32_t *idx, float *val_sel, bool begun, bool hist0_done)
 {
     if (len <= kSelSmallMax) {
         SAMS_LAUNCH_ON(ctx, stream, KID_SEL_SMALL, k_sel_small, 1, 1024, keys, len, (uint32_t)k, idx, val_sel);
@@ -447,10 +450,11 @@ int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, cons
     if (nt > sc.ntile_cap) return SAMS_EINVAL;
     uint32_t *cnt_gt = sc.cnt, *cnt_eq = sc.cnt + sc.ntile_cap;
     uint32_t *sel_base = sc.base, *eq_base = sc.base + sc.ntile_cap;
-    SAMS_LAUNCH_ON(ctx, stream, KID_SEL_INIT, k_sel_init, 1, 256, sc.sel, (uint32_t)k, sc.hist);
+    if (!begun) SAMS_TRY(enqueue_select_begin(ctx, stream, sc, k));
     for (int pass = 0; pass < kSelPasses; ++pass) {
-        SAMS_LAUNCH_ON(ctx, stream, KID_SEL_HIST, k_sel_hist, grid_for(len, 256 * 16, 4096), 256, keys, len, pass,
-                       sc.sel, sc.hist);
+        if (pass > 0 || !(begun && hist0_done))
+            SAMS_LAUNCH_ON(ctx, stream, KID_SEL_HIST, k_sel_hist, grid_for(len, 256 * 16, 4096), 256, keys, len, pass,
+                           sc.sel, sc.hist);
         SAMS_LAUNCH_ON(ctx, stream, KID_SEL_PICK, k_sel_pick, 1, 1024, sc.sel, sc.hist, pass);
     }
     const int waves_per_block = 256 / kWave;
@@ -468,7 +472,7 @@ int enqueue_select(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, cons
 int enqueue_refine(sams_ctx *ctx, hipStream_t stream, const SelScratch &sc, int32_t *pos, const int32_t *idx_in,
                    const float *delta_in, int64_t k_in, int64_t k_out, int32_t *idx_out, float *delta_out)
 {
-    SAMS_TRY(enqueue_select(ctx, stream, sc, delta_in, k_in, k_out, pos, delta_out));
+    SAMS_TRY(enqueue_select(ctx, stream, sc, delta_in, k_in, k_out, pos, delta_out, false, false));
     SAMS_LAUNCH_ON(ctx, stream, KID_REFINE_MAP, k_refine_map, grid_for(k_out, 256), 256, idx_in, pos, k_out, idx_out);
     SAMS_HIP(hipGetLastError());
     return SAMS_OK;

@@ -93,6 +93,13 @@ k_head(const float *__restrict__ g, float *__restrict__ m, float *__restrict__ e
 // ------------------------------------------------------------------------------------------
 // VEC = 4: four consecutive cells per thread with 16-byte loads (needs r*c to be a multiple of 4, so that
 // every worker's table starts on a 16-byte boundary)
+__device__ __forceinline__ float4 ld4_stream(const float *p)
+{
+    typedef float vec4f __attribute__((ext_vector_type(4)));
+    const vec4f t = __builtin_nontemporal_load(reinterpret_cast<const vec4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
 template <int VEC>
 __global__ void __launch_bounds__(256)
 k_reduce(const float *__restrict__ S_w, float *__restrict__ S_mean, int32_t n, int64_t rc)
@@ -102,13 +109,13 @@ k_reduce(const float *__restrict__ S_w, float *__restrict__ S_mean, int32_t n, i
     const float fn = (float)n;
     for (; t < rc; t += st) {
         if constexpr (VEC == 4) {
-            float4 acc = *reinterpret_cast<const float4 *>(S_w + t);
+            float4 acc = ld4_stream(S_w + t);                        // every table is read once: streaming loads
             for (int32_t i0 = 1; i0 < n; i0 += 8) {                  // eight tables' loads in flight, added in worker order
                 float4 b[8];
 #pragma unroll
                 for (int z = 0; z < 8; ++z) {
                     const int32_t i = (i0 + z < n) ? (i0 + z) : (n - 1);
-                    b[z] = *reinterpret_cast<const float4 *>(S_w + (int64_t)i * rc + t);
+                    b[z] = ld4_stream(S_w + (int64_t)i * rc + t);
                 }
 #pragma unroll
                 for (int z = 0; z < 8; ++z) {

@@ -27,11 +27,11 @@ def sams():
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
     "default": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
-                    sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=1, acc_wide=1),
+                    sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=1, acc_wide=2),
     "worker-major-staging": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
                                  sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1,
                                  stage_interleave=0, acc_wide=0),
-    "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=16,
+    "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=4,
                                  scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, run_pad=32,
                           scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=0, stage_interleave=0, acc_wide=0),
@@ -43,7 +43,7 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
                         scatter_threads=1024, sketch_path=3, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "fused-head": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
                        scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
-    "fused-head-small-tiles": dict(tile_log2=9, win_log2=7, chunk_log2=9, acc_threads=256, run_pad=16,
+    "fused-head-small-tiles": dict(tile_log2=9, win_log2=7, chunk_log2=9, acc_threads=256, run_pad=8,
                                    scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "fused-head-per-worker": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=32,
                                   scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
@@ -56,15 +56,21 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
     "interleaved-staging": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16,
                                 scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0, fuse_median=1,
                                 stage_interleave=1, acc_wide=0),
-    "interleaved-staging-row-groups": dict(tile_log2=11, win_log2=9, chunk_log2=8, acc_threads=256, run_pad=16,
+    "interleaved-staging-row-groups": dict(tile_log2=11, win_log2=9, chunk_log2=8, acc_threads=256, run_pad=4,
                                            scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=2,
                                            fuse_median=1, stage_interleave=1, acc_wide=0),
     "interleaved-staging-unfused": dict(tile_log2=10, win_log2=8, chunk_log2=11, acc_threads=512, run_pad=32,
                                         scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0,
                                         fuse_median=0, stage_interleave=1, acc_wide=0),
-    "accumulate-16-byte-loads": dict(tile_log2=12, win_log2=10, chunk_log2=11, acc_threads=1024, run_pad=16,
+    "accumulate-16-byte-loads": dict(tile_log2=12, win_log2=10, chunk_log2=11, acc_threads=1024, run_pad=8,
                                      scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0,
                                      fuse_median=1, stage_interleave=1, acc_wide=1),
+    "chunk-records": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=16,
+                          scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0,
+                          fuse_median=1, stage_interleave=1, acc_wide=2),
+    "chunk-records-worker-major": dict(tile_log2=13, win_log2=14, chunk_log2=11, acc_threads=1024, run_pad=32,
+                                       scatter_threads=512, sketch_path=2, estimate_path=0, fuse_head=0, stage_rows=2,
+                                       fuse_median=1, stage_interleave=0, acc_wide=2),
     "accumulate-16-byte-loads-worker-major": dict(tile_log2=10, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=32,
                                                   scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0,
                                                   stage_rows=2, fuse_median=1, stage_interleave=0, acc_wide=1),
@@ -185,6 +191,24 @@ def test_sketch_accumulate_float_within_tolerance(sams, path, wl, d):
         # binned path: terms are added in ascending coordinate order, exactly like the oracle's loop
         o32 = Oracle("f32")
         assert np.array_equal(got32, np.stack([o32.sketch(uh[i], hp, w.c) for i in range(w.n)]))
+
+
+@pytest.mark.parametrize("d,c", [(262_144, 100_000), (70_001, 400)])
+def test_sketch_accumulate_keeps_subnormal_sums(sams, path, d, c):
+    """Values that are small multiples of 2^-140: every partial sum is exact and subnormal, so the tables must equal
+    the oracle's bit for bit on every path -- unless some add flushes subnormal numbers to zero."""
+    n, r, k = 3, 5, 10
+    hp = inputs.hash_params(r, seed=9)
+    ints = inputs.integer_vectors(n, d, amax=16, seed=d + 1).numpy()
+    u = (ints.astype(np.float64) * 2.0 ** -140).astype(np.float32)
+    assert np.any(u != 0) and np.all(np.abs(u) < np.finfo(np.float32).tiny)
+    o = Oracle("f32")
+    want = np.stack([o.sketch(u[i], hp, c) for i in range(n)])
+    assert np.any(want != 0)
+    with sams.Context(d, n, r, c, k, hp) as ctx:
+        S = torch.empty((n, r, c), device="cuda")
+        ctx.sketch_accumulate(dev(u), S)
+        assert np.array_equal(host(S), want)
 
 
 @pytest.mark.parametrize("n,r,c", [(4, 5, 2048), (8, 5, 100_003), (16, 7, 5000), (3, 2, 17), (1, 1, 1)])

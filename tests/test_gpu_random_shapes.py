@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
 DEFAULTS = dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
-                sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=1, acc_wide=1)
+                sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=1, acc_wide=2)
 
 
 def dev(a):
@@ -45,7 +45,7 @@ def sample(rng):
         tun["acc_threads"] = int(rng.choice([t for t in (256, 512, 1024) if t <= (1 << chunk)] or [0]))
         if tun["acc_threads"] == 0:
             tun["chunk_log2"] = 0
-        tun["run_pad"] = int(rng.choice([16, 32]))
+        tun["run_pad"] = int(rng.choice([4, 8, 16, 32]))
         tun["scatter_threads"] = int(rng.choice([256, 512, 1024]))
     tun["sketch_path"] = int(rng.choice([0, 0, 2, 2, 3, 1]))
     tun["estimate_path"] = int(rng.choice([0, 0, 0, 1]))
@@ -53,7 +53,7 @@ def sample(rng):
     tun["fuse_median"] = int(rng.choice([1, 1, 0]))
     tun["stage_rows"] = int(rng.choice([0, 0, 1, 2, 3]))
     tun["stage_interleave"] = int(rng.integers(0, 2))
-    tun["acc_wide"] = int(rng.integers(0, 2))
+    tun["acc_wide"] = int(rng.integers(0, 3))
     return (d, n, r, c, k), tun
 
 
