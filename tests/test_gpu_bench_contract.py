@@ -39,6 +39,20 @@ def test_bench_prints_one_json_line_with_the_contract_fields(extra):
     assert r["launches_per_step"] >= 1.0 and r["kernel"] in j["kernels_ms_per_step"]
     if r["achieved"] is not None:
         assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12
+    assert r["peak_measured_copy"] > 100.0 and "traffic_from" in r
+    assert min(j["ms_per_step_min_max"]) <= j["ms_per_step_median"] <= max(j["ms_per_step_min_max"])
     c = j["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0.0 and c["unit"] == "coords/s" and c["sample"]
+    ct = j["cpu_baseline_threads"]
+    assert ct["kind"] == "oracle" and ct["cores"] >= 1 and ct["value"] > 0.0 and ct["same_result_as_single_thread"] is True
+
+
+@pytest.mark.timeout(300)
+def test_bench_times_both_memory_states_in_one_run():
+    p = run_bench("--workload", "C1", "--steps", "3", "--warmup", "1", "--no-cpu-baseline")
+    assert p.returncode == 0, p.stderr[-2000:]
+    j = json.loads([ln for ln in p.stdout.splitlines() if ln.strip()][-1])
+    assert j["config"]["vram_preconditioned"] is True
+    f = j["fresh_memory_state"]
+    assert f["ms_per_step"] > 0.0 and f["value"] > 0.0
 
