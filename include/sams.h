@@ -104,9 +104,10 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 0: one contiguous copy per (worker, row).  Same results either way.
  *   "acc_wide"    2 (default), 1 or 0: with 1024 threads and 2048-position chunks the binned accumulation reads its
  *                 streams with 16-byte loads instead of 4-byte loads (1, 2), and with 2 the per-position metadata
- *                 (4 bytes) is replaced by per-chunk records (2-byte codes plus a short list of the positions that
- *                 share a bucket inside the chunk: 2.5 bytes per position).  A context whose hashes put more than
- *                 256 such positions into one chunk (small or badly filled windows) falls back to 1.  Same results.
+ *                 (4 bytes) is replaced by per-chunk records (2-byte codes plus a list of the groups of positions
+ *                 that share a bucket inside a chunk of 4096: 2.5 bytes per position) and a thread keeps the values
+ *                 of its four positions in registers.  Decided per row: a row whose hash gives some chunk more than
+ *                 512 such groups, 1024 such positions or a group of more than 127 keeps the meta words.  Same results.
  *   "fuse_median" 1 (default) or 0: with 1 the plan-driven recovery keeps the row estimates in registers
  *                 (needs r <= 6 with tiles of 2^14, r <= 12 with 2^13, any r with 2^12 or less); with 0
  *                 they go through a [r][d] scratch array
@@ -128,10 +129,13 @@ int sams_destroy(sams_ctx *ctx);
  * (c fits one window), 2 = the binned, order-preserving path.  -1 for a NULL context. */
 int sams_sketch_mode(const sams_ctx *ctx);
 
-/* Which kernel carries out the second pass of the binned path for this context: 0 = 4-byte loads, 1 = 16-byte loads
- * of values and per-position meta words, 2 = 16-byte loads of values and compact chunk records (see "acc_wide").
- * -1 when the context does not use the binned path (or is NULL). */
+/* How the second pass of the binned path reads its metadata in this context (see "acc_wide"): 2 = every row through
+ * compact chunk records; 1 or 0 = some or all rows through per-position meta words, with 16-byte (1) or 4-byte (0)
+ * loads.  -1 when the context does not use the binned path (or is NULL).
+ * sams_record_rows: bit j set = row j goes through chunk records (decided per row when the plan is built: a row whose
+ * hash puts too many positions of one 4096-position chunk into shared buckets keeps its meta words); -1 as above. */
 int sams_accumulate_variant(const sams_ctx *ctx);
+int64_t sams_record_rows(const sams_ctx *ctx);
 
 /* Device bytes the context allocated. */
 int64_t sams_scratch_bytes(const sams_ctx *ctx);

@@ -216,6 +216,11 @@ int sams_accumulate_variant(const sams_ctx *ctx)
     return (ctx && ctx->plan.mode == PLAN_BINNED) ? ctx->plan.acc_variant : -1;
 }
 
+int64_t sams_record_rows(const sams_ctx *ctx)
+{
+    return (ctx && ctx->plan.mode == PLAN_BINNED) ? (int64_t)ctx->plan.rec_mask : -1;
+}
+
 int64_t sams_scratch_bytes(const sams_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }
 
 int64_t sams_precondition_device_memory(double fraction)

@@ -66,7 +66,8 @@ enum PlanMode { PLAN_ATOMIC = 0, PLAN_LDS_ROW = 1, PLAN_BINNED = 2 };
 // static permutation "coordinate order -> bucket order" of the binned path (see sams_plan.hip)
 struct Plan {
     int mode;
-    int acc_variant;    // pass 2: 0 = 4-byte loads, 1 = 16-byte loads of values and meta words, 2 = 16-byte loads of values and chunk records
+    int acc_variant;    // pass 2 of the rows that read meta words: 0 = 4-byte loads, 1 = 16-byte loads; 2 = no such row (all rows read chunk records)
+    uint32_t rec_mask;  // bit j set: row j reads chunk records in pass 2 (k_bin_accumulate_r)
     int win_log2, tile_log2, chunk_log2, acc_threads, run_pad, grp_log2, stage_rows, stage_ilv, acc_wide;
     int64_t nbins, ntile, dpad, rowlen;
     uint16_t *srcp;     // [r][rowlen]      slot -> coordinate inside its tile (bits 0-14) and sign (bit 15), or padding

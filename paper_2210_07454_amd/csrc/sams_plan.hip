@@ -85,6 +85,12 @@ struct RowGroup {
 };
 constexpr int kIlvLog2 = 5;
 
+// the rows (absolute numbers, all inside the row group at hand) one launch of an accumulate kernel handles
+struct RowSel {
+    int32_t cnt;
+    int8_t row[SAMS_MAX_ROWS];
+};
+
 // start of worker i's copy of staged row jj, and the offset of stream position p from there
 __device__ __forceinline__ int64_t stage_row(const RowGroup &rg, int32_t n, int64_t rowlen, int32_t i, int32_t jj)
 {
@@ -329,7 +335,7 @@ k_plan_chain(int chunk_log2, int64_t rowlen, uint32_t *__restrict__ meta)
 // ------------------------------------------------------------------------------------------
 // One workgroup per (row, chunk of 4096 positions): sorts the chunk's positions by (bucket, position), finds the
 // groups that share a bucket and writes the record.  `over` is set when a chunk does not fit the record format
-// (too many chains or chain positions, or too long a chain): the caller then keeps the meta words.
+// (too many chains or chain positions, or too long a chain), per row (over[row]): such rows keep their meta words.
 __global__ void __launch_bounds__(kPlanThreads)
 k_plan_records(const uint32_t *__restrict__ meta, uint32_t *__restrict__ rec, int64_t rowlen, uint32_t *__restrict__ over)
 {
@@ -404,9 +410,9 @@ k_plan_records(const uint32_t *__restrict__ meta, uint32_t *__restrict__ rec, in
     }
     if (t == kPlanThreads - 1) {
         nchains = e;
-        if (e > (uint32_t)kRecChains || rank > (uint32_t)kRecRanks) atomicOr(over, 1u);
+        if (e > (uint32_t)kRecChains || rank > (uint32_t)kRecRanks) atomicOr(over + blockIdx.y, 1u);
     }
-    if (too_long) atomicOr(over, 1u);
+    if (too_long) atomicOr(over + blockIdx.y, 1u);
     __syncthreads();
     for (uint32_t q = nchains + (uint32_t)t; q < (uint32_t)kRecChains; q += kPlanThreads) rc[kRecCodeWords + q] = 0u;   // unused entries
 }
@@ -760,7 +766,7 @@ k_head_sparse_v_wide(const float *__restrict__ g, const int32_t *__restrict__ id
 template <int THREADS, int UNROLL>
 __global__ void __launch_bounds__(THREADS)
 k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ meta,
-                 const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg,
+                 const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg, RowSel sel,
                  int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
 {
     constexpr int CH = THREADS * UNROLL;
@@ -772,8 +778,8 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
     const int64_t slot = id / kNumXcd;
     const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
     const int32_t i = (int32_t)(slot % n);
-    if (group >= (int64_t)rg.rj * nbins) return;
-    const int32_t jj = (int32_t)(group / nbins), j = rg.j0 + jj;
+    if (group >= (int64_t)sel.cnt * nbins) return;
+    const int32_t j = sel.row[group / nbins], jj = j - rg.j0;
     const int64_t bin = group % nbins;
     for (int t = threadIdx.x; t < W; t += THREADS) win[t] = 0.f;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
@@ -854,7 +860,7 @@ k_bin_accumulate(const float *__restrict__ stg, const uint32_t *__restrict__ met
 // consecutive positions and works as in k_bin_accumulate.  Same order of additions, same results.
 __global__ void __launch_bounds__(1024)
 k_bin_accumulate_q(const float *__restrict__ stg, const uint32_t *__restrict__ meta,
-                   const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg,
+                   const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg, RowSel sel,
                    int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
 {
     constexpr int CH = 2048;
@@ -867,8 +873,8 @@ k_bin_accumulate_q(const float *__restrict__ stg, const uint32_t *__restrict__ m
     const int64_t slot = id / kNumXcd;
     const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
     const int32_t i = (int32_t)(slot % n);
-    if (group >= (int64_t)rg.rj * nbins) return;
-    const int32_t jj = (int32_t)(group / nbins), j = rg.j0 + jj;
+    if (group >= (int64_t)sel.cnt * nbins) return;
+    const int32_t j = sel.row[group / nbins], jj = j - rg.j0;
     const int64_t bin = group % nbins;
     for (int t = threadIdx.x; t < W; t += 1024) win[t] = 0.f;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
@@ -1017,7 +1023,7 @@ __device__ __forceinline__ void acc_r_chunks(const vec4f *__restrict__ vsrc, int
 
 __global__ void __launch_bounds__(1024)
 k_bin_accumulate_r(const float *__restrict__ stg, const uint32_t *__restrict__ rec,
-                   const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg,
+                   const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg, RowSel sel,
                    int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
 {
     constexpr int CH = kRecChunk;
@@ -1030,8 +1036,8 @@ k_bin_accumulate_r(const float *__restrict__ stg, const uint32_t *__restrict__ r
     const int64_t slot = id / kNumXcd;
     const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
     const int32_t i = (int32_t)(slot % n);
-    if (group >= (int64_t)rg.rj * nbins) return;
-    const int32_t jj = (int32_t)(group / nbins), j = rg.j0 + jj;
+    if (group >= (int64_t)sel.cnt * nbins) return;
+    const int32_t j = sel.row[group / nbins], jj = j - rg.j0;
     const int64_t bin = group % nbins;
     const int64_t b0 = binbase[(int64_t)j * (nbins + 1) + bin], b1 = binbase[(int64_t)j * (nbins + 1) + bin + 1];
     const int64_t nchunk = (b1 - b0) / CH;                           // bins are whole chunks (see plan_create)
@@ -1376,7 +1382,7 @@ static int dev_alloc(sams_ctx *ctx, void **p, int64_t bytes)
 
 // (threads, unroll) variants of the accumulate kernel, selected by acc_threads / chunk_log2
 template <int TH, int UN>
-static int launch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_attr)
+static int launch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, RowSel sel, bool set_attr)
 {
     Plan &pl = ctx->plan;
     const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * TH * UN * sizeof(uint2);
@@ -1385,15 +1391,17 @@ static int launch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_att
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
         return SAMS_OK;
     }
-    const int64_t groups = (int64_t)rg.rj * pl.nbins;
+    const int64_t groups = (int64_t)sel.cnt * pl.nbins;
     const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
     ProfScope ps(ctx, KID_BIN_ACCUMULATE);
     hipLaunchKernelGGL((k_bin_accumulate<TH, UN>), dim3((unsigned)(gpad * ctx->n)), dim3(TH), lds, ctx->stream,
-                       pl.stg, pl.meta, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins,
+                       pl.stg, pl.meta, pl.binbase, S_workers, ctx->n, rg, sel, ctx->c, pl.win_log2, pl.nbins,
                        pl.rowlen);
     return SAMS_OK;
 }
 
+// Pass 2 for the rows of one row group: the rows whose chunks fit the record format (pl.rec_mask) go to the kernel
+// that reads chunk records, the others to a kernel that reads meta words.
 static int dispatch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_attr)
 {
     const Plan &pl = ctx->plan;
@@ -1402,23 +1410,31 @@ static int dispatch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_a
         SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate_q, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
         SAMS_HIP(hipFuncSetAttribute((const void *)k_bin_accumulate_r, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     }
-    if (!set_attr && pl.acc_variant >= 1) {
-        const int64_t groups = (int64_t)rg.rj * pl.nbins;
+    RowSel with_rec = {0, {0}}, with_meta = {0, {0}};
+    for (int32_t j = rg.j0; j < rg.j0 + rg.rj; ++j) {
+        RowSel &dst = ((pl.rec_mask >> j) & 1u) ? with_rec : with_meta;
+        dst.row[dst.cnt++] = (int8_t)j;
+    }
+    if (!set_attr && with_rec.cnt > 0) {
+        const int64_t groups = (int64_t)with_rec.cnt * pl.nbins;
         const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
+        const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * (kRecRanks + kRecPadRanks) * 4 + (size_t)2 * kRecChains * 4;
         ProfScope ps(ctx, KID_BIN_ACCUMULATE);
-        if (pl.acc_variant == 2) {
-            const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * (kRecRanks + kRecPadRanks) * 4 + (size_t)2 * kRecChains * 4;
-            hipLaunchKernelGGL(k_bin_accumulate_r, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
-                               pl.rec, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
-        } else {
-            const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)4 * 2048 * 4;
-            hipLaunchKernelGGL(k_bin_accumulate_q, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
-                               pl.meta, pl.binbase, S_workers, ctx->n, rg, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
-        }
+        hipLaunchKernelGGL(k_bin_accumulate_r, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
+                           pl.rec, pl.binbase, S_workers, ctx->n, rg, with_rec, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
+    }
+    if (!set_attr && with_meta.cnt == 0) return SAMS_OK;
+    if (!set_attr && pl.acc_variant >= 1) {
+        const int64_t groups = (int64_t)with_meta.cnt * pl.nbins;
+        const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
+        const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)4 * 2048 * 4;
+        ProfScope ps(ctx, KID_BIN_ACCUMULATE);
+        hipLaunchKernelGGL(k_bin_accumulate_q, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
+                           pl.meta, pl.binbase, S_workers, ctx->n, rg, with_meta, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);
         return SAMS_OK;
     }
 #define SAMS_ACC(TH, UN) \
-    if (pl.acc_threads == TH && un == UN) return launch_acc<TH, UN>(ctx, S_workers, rg, set_attr);
+    if (pl.acc_threads == TH && un == UN) return launch_acc<TH, UN>(ctx, S_workers, rg, with_meta, set_attr);
     SAMS_ACC(1024, 1) SAMS_ACC(1024, 2) SAMS_ACC(512, 1) SAMS_ACC(512, 2) SAMS_ACC(512, 4)
     SAMS_ACC(256, 1) SAMS_ACC(256, 2) SAMS_ACC(256, 4) SAMS_ACC(256, 8)
 #undef SAMS_ACC
@@ -1587,28 +1603,32 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
             if (*tmp[q]) { (void)hipFree(*tmp[q]); *tmp[q] = nullptr; }
         // which accumulate kernel: the generic one, the one with 16-byte loads, or the one reading chunk records
         pl.acc_variant = (wide_shape && pl.acc_wide >= 1) ? 1 : 0;
+        pl.rec_mask = 0;
         if (wide_shape && pl.acc_wide >= 2) {
-            uint32_t *over = nullptr, h_over = 0;
-            if (hipMalloc((void **)&over, 4) != hipSuccess) { (void)hipGetLastError(); rc = SAMS_ENOMEM; break; }
+            uint32_t *over = nullptr, h_over[SAMS_MAX_ROWS] = {0};
+            if (hipMalloc((void **)&over, SAMS_MAX_ROWS * 4) != hipSuccess) { (void)hipGetLastError(); rc = SAMS_ENOMEM; break; }
             rc = dev_alloc(ctx, (void **)&pl.rec, r * (rowlen / kRecChunk) * kRecWords * 4);
-            if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, over, 1, 0u);
+            if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, over, SAMS_MAX_ROWS, 0u);
             if (rc == SAMS_OK) {
                 ProfScope ps(ctx, KID_PLAN_BUILD);
                 hipLaunchKernelGGL(k_plan_records, dim3((unsigned)(rowlen / kRecChunk), (unsigned)r), dim3(kPlanThreads), 0,
                                    ctx->stream, pl.meta, pl.rec, rowlen, over);
-                e = hipMemcpyAsync(&h_over, over, 4, hipMemcpyDeviceToHost, ctx->stream);
+                e = hipMemcpyAsync(h_over, over, SAMS_MAX_ROWS * 4, hipMemcpyDeviceToHost, ctx->stream);
                 if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
                 if (e == hipSuccess) e = hipGetLastError();
                 if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; }
             }
             (void)hipFree(over);
             if (rc != SAMS_OK) break;
-            if (!h_over) {                                           // every chunk fits the record format: the meta words can go
+            // rows every chunk of which fits the record format use the records; the others keep their meta words
+            for (int64_t j = 0; j < r; ++j)
+                if (!h_over[j]) pl.rec_mask |= 1u << j;
+            if (pl.rec_mask == (r >= 32 ? 0xffffffffu : ((1u << r) - 1u))) {
                 pl.acc_variant = 2;
                 (void)hipFree(pl.meta);
                 pl.meta = nullptr;
                 ctx->scratch_bytes -= r * rowlen * 4;
-            } else {
+            } else if (pl.rec_mask == 0) {
                 (void)hipFree(pl.rec);
                 pl.rec = nullptr;
                 ctx->scratch_bytes -= r * (rowlen / kRecChunk) * kRecWords * 4;

@@ -21,7 +21,7 @@ _ERR = {SAMS_EINVAL: "SAMS_EINVAL (bad argument)", SAMS_ENOMEM: "SAMS_ENOMEM (sc
 
 # every symbol include/sams.h declares
 EXPORTS = ["sams_create", "sams_destroy", "sams_scratch_bytes", "sams_precondition_device_memory", "sams_last_hip_error", "sams_hash_dump",
-           "sams_configure", "sams_sketch_mode", "sams_accumulate_variant", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_only", "sams_profile_read",
+           "sams_configure", "sams_sketch_mode", "sams_accumulate_variant", "sams_record_rows", "sams_profile_kernels", "sams_profile_name", "sams_profile_enable", "sams_profile_only", "sams_profile_read",
            "sketch_accumulate", "sketch_reduce", "unsketch_topk", "unsketch_estimates", "gather_topk", "topk_refine",
            "amsgrad_ef_update", "amsgrad_ef_update_pa", "topk_refine_static", "topk_refine_static_max_candidates"]
 
@@ -58,6 +58,8 @@ def load() -> ctypes.CDLL:
     lib.sams_configure.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.sams_sketch_mode.argtypes = [vp]
     lib.sams_accumulate_variant.argtypes = [vp]
+    lib.sams_record_rows.argtypes = [vp]
+    lib.sams_record_rows.restype = i64
     lib.sams_profile_kernels.argtypes = []
     lib.sams_profile_name.argtypes = [ctypes.c_int]
     lib.sams_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -76,7 +78,7 @@ def load() -> ctypes.CDLL:
     lib.topk_refine_static_max_candidates.restype = i64
     for name in EXPORTS:
         if name not in ("sams_scratch_bytes", "sams_profile_name", "sams_precondition_device_memory",
-                        "topk_refine_static_max_candidates"):
+                        "topk_refine_static_max_candidates", "sams_record_rows"):
             getattr(lib, name).restype = ctypes.c_int
     lib.sams_profile_name.restype = ctypes.c_char_p
     _lib = lib
@@ -172,6 +174,11 @@ class Context:
     @property
     def accumulate_variant(self) -> int:
         return int(self._lib.sams_accumulate_variant(self._h))
+
+    @property
+    def record_rows(self) -> int:
+        """Bit mask of the rows whose second pass reads chunk records (see sams.h)."""
+        return int(self._lib.sams_record_rows(self._h))
 
     def sams_profile_enable(self, on: bool):
         _check(self._lib.sams_profile_enable(self._h, 1 if on else 0), "sams_profile_enable")

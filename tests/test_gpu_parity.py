@@ -211,6 +211,32 @@ def test_sketch_accumulate_keeps_subnormal_sums(sams, path, d, c):
         assert np.array_equal(host(S), want)
 
 
+def test_rows_choose_between_chunk_records_and_meta_words_one_by_one(sams):
+    """Row 0's bucket hash multiplies by c (a power of two), so that thousands of consecutive coordinates share a
+    bucket: its chunks do not fit the record format and it keeps its meta words, while the other rows use records.
+    The tables must equal the sequential sum bit for bit either way, also when rows are staged in groups."""
+    d, n, r, c, k = 300_000, 3, 4, 1 << 17, 100
+    hp = inputs.hash_params(r, seed=12)
+    hp[0, 0] = c
+    rng = np.random.default_rng(3)
+    u = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-4, 0, (n, d))).astype(np.float32)
+    o = Oracle("f32")
+    want = np.stack([o.sketch(u[i], hp, c) for i in range(n)])
+    try:
+        for rows in (0, 3):
+            for key, val in dict(PATHS["chunk-records"], stage_rows=rows).items():
+                sams.sams_configure(key, val)
+            with sams.Context(d, n, r, c, k, hp) as ctx:
+                mask = ctx.record_rows
+                assert mask & 1 == 0 and mask != 0 and ctx.accumulate_variant == 1, mask
+                S = torch.empty((n, r, c), device="cuda")
+                ctx.sketch_accumulate(dev(u), S)
+                assert np.array_equal(host(S), want)
+    finally:
+        for key, val in PATHS["default"].items():
+            sams.sams_configure(key, val)
+
+
 @pytest.mark.parametrize("n,r,c", [(4, 5, 2048), (8, 5, 100_003), (16, 7, 5000), (3, 2, 17), (1, 1, 1)])
 def test_sketch_reduce_bit_exact(sams, n, r, c):
     rng = np.random.default_rng(c)
@@ -449,14 +475,33 @@ def near_threshold(est, k, idx_a, idx_b):
     return diff, bool(np.all(np.abs(mag[diff] - tau) <= TOL * tau))
 
 
-@pytest.mark.parametrize("wl,d,steps", [("C1", 65_536, 10), ("C2", 400_000, 6), ("C3", 300_000, 5),
-                                        ("C4", 600_000, 5), ("C5", 500_000, 3), ("P1", 500_000, 3),
-                                        ("P2a", 60_000, 4), ("P2b", 60_000, 3)])
-def test_chained_steps_follow_the_oracle(sams, path, wl, d, steps):
+CHAIN_WORKLOADS = [("C1", 65_536, 10), ("C2", 400_000, 6), ("C3", 300_000, 5), ("C4", 600_000, 5), ("C5", 500_000, 3),
+                   ("P1", 300_000, 3), ("P2a", 60_000, 4), ("P2b", 60_000, 3)]
+
+
+def chain_cases():
+    """A covering set instead of the full product: the default launch configuration runs every workload, every other
+    configuration runs three of them (dealt round-robin, so that every workload meets seven or eight configurations)."""
+    cases = [("default", *wl) for wl in CHAIN_WORKLOADS]
+    others = [name for name in PATHS if name != "default"]
+    for q, name in enumerate(others):
+        for z in range(3):
+            cases.append((name, *CHAIN_WORKLOADS[(3 * q + z) % len(CHAIN_WORKLOADS)]))
+    return cases
+
+
+@pytest.mark.parametrize("path_name,wl,d,steps", chain_cases())
+def test_chained_steps_follow_the_oracle(sams, path_name, wl, d, steps):
     """Free-running GPU run; at every step the oracle is restarted from the GPU's previous state, so
     each step is compared on real evolving state (bitmap of I_{t-1}, error feedback, vhat)."""
-    w = inputs.WORKLOADS[wl].scaled(d)
-    run_chain(sams, w, steps, lambda t: w.lr)
+    for key, val in PATHS[path_name].items():
+        sams.sams_configure(key, val)
+    try:
+        w = inputs.WORKLOADS[wl].scaled(d)
+        run_chain(sams, w, steps, lambda t: w.lr)
+    finally:
+        for key, val in PATHS["default"].items():
+            sams.sams_configure(key, val)
 
 
 @pytest.mark.parametrize("wl,d,steps", [("C1", 65_536, 8), ("P2a", 60_000, 5), ("C4", 300_000, 4)])
