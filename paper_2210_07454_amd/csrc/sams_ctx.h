@@ -202,21 +202,24 @@ __device__ __forceinline__ float median_of(float (&a)[R])
     return a[(R - 1) / 2];
 }
 
-// exclusive prefix sum over the 1024 threads of a block (part: 1024 words of LDS)
+// exclusive prefix sum over the 1024 threads of a block (part: at least 16 words of LDS; all threads call it):
+// a shuffle scan inside every wavefront, then the 16 wavefront totals through LDS
 __device__ __forceinline__ uint32_t block_exclusive_scan_1024(uint32_t val, uint32_t *part)
 {
-    const int t = threadIdx.x;
-    part[t] = val;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-        const uint32_t x = t >= off ? part[t - off] : 0u;
-        __syncthreads();
-        part[t] += x;
-        __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    uint32_t incl = val;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t x = __shfl_up(incl, off);
+        if (lane >= off) incl += x;
     }
-    const uint32_t excl = part[t] - val;
+    if (lane == kWave - 1) part[wave] = incl;
     __syncthreads();
-    return excl;
+    uint32_t before = 0;
+#pragma unroll
+    for (int q = 0; q < 1024 / kWave; ++q) before += q < wave ? part[q] : 0u;
+    __syncthreads();
+    return before + incl - val;
 }
 
 // ---- enqueue functions (all asynchronous on ctx->stream; return SAMS_OK or SAMS_EHIP) ----

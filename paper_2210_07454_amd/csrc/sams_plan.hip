@@ -340,7 +340,7 @@ __global__ void __launch_bounds__(kPlanThreads)
 k_plan_records(const uint32_t *__restrict__ meta, uint32_t *__restrict__ rec, int64_t rowlen, uint32_t *__restrict__ over)
 {
     __shared__ uint32_t keys[kRecChunk];
-    __shared__ uint32_t part[1024];
+    __shared__ uint32_t part[16];
     __shared__ uint32_t nchains;
     const int t = threadIdx.x;
     const int64_t nchunk = rowlen / kRecChunk;
@@ -1097,9 +1097,23 @@ k_bin_lookup(const float *__restrict__ S_mean, const uint16_t *__restrict__ wlow
     const int64_t n4 = (b1 - b0) >> 2;
     const int64_t piece = (n4 + nsplit - 1) / nsplit;
     const int64_t q1 = (part + 1) * piece < n4 ? (part + 1) * piece : n4;
-    for (int64_t q = part * piece + threadIdx.x; q < q1; q += blockDim.x) {
-        const uint2 w = load_stream2(m4 + q);
-        store_stream(o4 + q, make_float4(win[w.x & 0xffffu], win[w.x >> 16], win[w.y & 0xffffu], win[w.y >> 16]));
+    // four steps' buckets are fetched before the first is used (clamped addresses past the piece's end: read, not
+    // used), so that a thread has 32 bytes in flight instead of 8
+    constexpr int kAhead = 4;
+    for (int64_t q = part * piece + threadIdx.x; q < q1; q += (int64_t)blockDim.x * kAhead) {
+        uint2 w[kAhead];
+#pragma unroll
+        for (int z = 0; z < kAhead; ++z) {
+            const int64_t qz = q + (int64_t)z * blockDim.x;
+            w[z] = load_stream2(m4 + (qz < q1 ? qz : q1 - 1));
+        }
+#pragma unroll
+        for (int z = 0; z < kAhead; ++z) {
+            const int64_t qz = q + (int64_t)z * blockDim.x;
+            if (qz < q1)
+                store_stream(o4 + qz, make_float4(win[w[z].x & 0xffffu], win[w[z].x >> 16], win[w[z].y & 0xffffu],
+                                                  win[w[z].y >> 16]));
+        }
     }
 }
 
@@ -1144,7 +1158,7 @@ k_bin_collect(const float *__restrict__ lk, const uint16_t *__restrict__ srcp, c
 // k_bin_collect with the median of Sec. II-C and the 1/sqrt(vhat) scaling of Alg. 3 fused in: each thread
 // keeps the R row estimates of its 4 * ITERS coordinates in registers (tiles of at most 4096 * ITERS
 // coordinates), so the per-row estimates never go to memory.
-constexpr int kCollectAhead = 3;
+constexpr int kCollectAhead = 4;
 
 template <int R, int ITERS>
 __global__ void __launch_bounds__(kFusedThreads)

@@ -135,7 +135,7 @@ k_sel_hist(const float *__restrict__ est, int64_t d, int pass, const SelState *_
 __global__ void __launch_bounds__(1024)
 k_sel_pick(SelState *st, uint32_t *hist, int pass)
 {
-    __shared__ uint32_t part[1024];
+    __shared__ uint32_t part[16];
     const int nb = 1 << sel_width(pass);
     const int t = threadIdx.x;
     const int b0 = nb - 1 - 2 * t, b1 = nb - 2 - 2 * t;             // descending bins
@@ -159,26 +159,35 @@ k_sel_pick(SelState *st, uint32_t *hist, int pass)
     }
 }
 
+// a lane's four keys against the threshold: adds to its counts of keys above tau and equal to it
+__device__ __forceinline__ void count_keys4(const Keys4 &q, uint32_t tau, uint32_t &ngt, uint32_t &neq)
+{
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        const uint32_t key = mag_key(q.v[z]);
+        const bool have = (q.have >> z) & 1u;
+        ngt += (have && key > tau) ? 1u : 0u;
+        neq += (have && key == tau) ? 1u : 0u;
+    }
+}
+
+// sums of the lanes' counts over the wavefront (in every lane)
+__device__ __forceinline__ void wave_sum2(uint32_t &a, uint32_t &b)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off);
+        b += __shfl_xor(b, off);
+    }
+}
+
 // one wavefront over the keys [base, base + span): how many exceed tau, how many equal it (in every lane)
 __device__ __forceinline__ void wave_count(const float *__restrict__ est, int64_t d, int64_t base, int span,
                                            uint32_t tau, int lane, uint32_t *gt_out, uint32_t *eq_out)
 {
     uint32_t ngt = 0, neq = 0;                                       // this lane's counts
-    for (int s = 0; s < span; s += kWave * 4) {
-        const Keys4 q = load_keys4(est, base + s + lane * 4, d);
-#pragma unroll
-        for (int z = 0; z < 4; ++z) {
-            const uint32_t key = mag_key(q.v[z]);
-            const bool have = (q.have >> z) & 1u;
-            ngt += (have && key > tau) ? 1u : 0u;
-            neq += (have && key == tau) ? 1u : 0u;
-        }
-    }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        ngt += __shfl_xor(ngt, off);
-        neq += __shfl_xor(neq, off);
-    }
+    for (int s = 0; s < span; s += kWave * 4) count_keys4(load_keys4(est, base + s + lane * 4, d), tau, ngt, neq);
+    wave_sum2(ngt, neq);
     *gt_out = ngt;
     *eq_out = neq;
 }
@@ -202,39 +211,101 @@ k_sel_count(const float *__restrict__ est, int64_t d, const SelState *__restrict
 // single block: exclusive prefixes over the tiles.  eq_base = equal keys before the tile;
 // sel_base = selected coordinates before the tile, where a tile contributes all its greater keys
 // and as many of its equal keys as are still wanted (k_eq counted from the smallest index).
+// Rounds of 1024 x kScanItems consecutive tiles; a thread owns kScanItems consecutive tiles of a round.
+constexpr int kScanItems = 8;
+
 __global__ void __launch_bounds__(1024)
 k_sel_scan(const uint32_t *__restrict__ cnt_gt, const uint32_t *__restrict__ cnt_eq, int64_t ntile,
            const SelState *__restrict__ st, uint32_t *__restrict__ sel_base,
            uint32_t *__restrict__ eq_base)
 {
-    __shared__ uint32_t part[1024];
+    __shared__ uint32_t part[16];
+    __shared__ uint32_t carry[2];
     const int t = threadIdx.x;
     const uint32_t k_eq = st->k_eq;
     uint32_t eq_run = 0, sel_run = 0;                                // totals of the rounds already done
-    for (int64_t q0 = 0; q0 < ntile; q0 += 1024) {                   // 1024 consecutive tiles per round
-        const int64_t q = q0 + t;
-        const uint32_t ce = q < ntile ? cnt_eq[q] : 0u, cg = q < ntile ? cnt_gt[q] : 0u;
-        const uint32_t eb = eq_run + block_exclusive_scan_1024(ce, part);
-        const uint32_t want = eb < k_eq ? k_eq - eb : 0u;
-        const uint32_t take = cg + (ce < want ? ce : want);
-        const uint32_t sb = sel_run + block_exclusive_scan_1024(take, part);
-        if (q < ntile) {
-            eq_base[q] = eb;
-            sel_base[q] = sb;
+    for (int64_t q0 = 0; q0 < ntile; q0 += 1024 * kScanItems) {
+        const int64_t lo = q0 + (int64_t)t * kScanItems;
+        uint32_t ce[kScanItems], cg[kScanItems];
+        uint32_t eq_sum = 0;
+#pragma unroll
+        for (int z = 0; z < kScanItems; ++z) {
+            ce[z] = lo + z < ntile ? cnt_eq[lo + z] : 0u;
+            cg[z] = lo + z < ntile ? cnt_gt[lo + z] : 0u;
+            eq_sum += ce[z];
         }
+        const uint32_t eb0 = eq_run + block_exclusive_scan_1024(eq_sum, part);
+        uint32_t eb = eb0, take_sum = 0;
+#pragma unroll
+        for (int z = 0; z < kScanItems; ++z) {
+            const uint32_t want = eb < k_eq ? k_eq - eb : 0u;
+            take_sum += cg[z] + (ce[z] < want ? ce[z] : want);
+            eb += ce[z];
+        }
+        uint32_t sb = sel_run + block_exclusive_scan_1024(take_sum, part);
         if (t == 1023) {
-            part[0] = eb + ce;
-            part[1] = sb + take;
+            carry[0] = eb;
+            carry[1] = sb + take_sum;
+        }
+        eb = eb0;
+#pragma unroll
+        for (int z = 0; z < kScanItems; ++z) {
+            const uint32_t want = eb < k_eq ? k_eq - eb : 0u;
+            if (lo + z < ntile) {
+                eq_base[lo + z] = eb;
+                sel_base[lo + z] = sb;
+            }
+            sb += cg[z] + (ce[z] < want ? ce[z] : want);
+            eb += ce[z];
         }
         __syncthreads();
-        eq_run = part[0];
-        sel_run = part[1];
+        eq_run = carry[0];
+        sel_run = carry[1];
         __syncthreads();
     }
 }
 
-// one wavefront walks the keys [base, base + span) in index order and writes the selected ones (key > tau, or
-// key == tau and among the first k_eq such keys) at their rank; out, eqr: selected and equal keys before base
+// One sweep of the ordered compaction: the wavefront's lanes hold four consecutive keys each, starting at coordinate
+// l0 in this lane; the selected ones (key > tau, or key == tau and among the first k_eq such keys) are written at
+// their rank.  out, eqr: selected and equal keys before this sweep, updated for the next one.
+__device__ __forceinline__ void compact_keys4(const Keys4 &q, int64_t l0, uint32_t tau, uint32_t k_eq, uint64_t below,
+                                              uint32_t &out, uint32_t &eqr, int64_t k, int32_t *__restrict__ idx,
+                                              float *__restrict__ est_sel)
+{
+    uint32_t gt = 0, eq = 0;                                         // bit z: key z is above / at the threshold
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        const uint32_t key = mag_key(q.v[z]);
+        const bool have = (q.have >> z) & 1u;
+        gt |= (have && key > tau) ? (1u << z) : 0u;
+        eq |= (have && key == tau) ? (1u << z) : 0u;
+    }
+    uint32_t eq_before, eq_total;
+    wave_prefix3((uint32_t)__popc(eq), below, &eq_before, &eq_total);
+    uint32_t take = gt;
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        const uint32_t rank = eqr + eq_before + (uint32_t)__popc(eq & ((1u << z) - 1u));
+        if (((eq >> z) & 1u) && rank < k_eq) take |= 1u << z;
+    }
+    uint32_t take_before, take_total;
+    wave_prefix3((uint32_t)__popc(take), below, &take_before, &take_total);
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+        if ((take >> z) & 1u) {
+            const int64_t pos = (int64_t)out + take_before + __popc(take & ((1u << z) - 1u));
+            if (pos < k) {
+                idx[pos] = (int32_t)(l0 + z);
+                if (est_sel) est_sel[pos] = q.v[z];
+            }
+        }
+    }
+    out += take_total;
+    eqr += eq_total;
+}
+
+// one wavefront walks the keys [base, base + span) in index order and writes the selected ones at their rank;
+// out, eqr: selected and equal keys before base
 __device__ __forceinline__ void wave_compact(const float *__restrict__ est, int64_t d, int64_t base, int span,
                                              uint32_t tau, uint32_t k_eq, int lane, uint32_t out, uint32_t eqr,
                                              int64_t k, int32_t *__restrict__ idx, float *__restrict__ est_sel)
@@ -242,37 +313,7 @@ __device__ __forceinline__ void wave_compact(const float *__restrict__ est, int6
     const uint64_t below = ((uint64_t)1 << lane) - 1;
     for (int s = 0; s < span; s += kWave * 4) {
         const int64_t l0 = base + s + lane * 4;                      // this lane's four consecutive keys
-        const Keys4 q = load_keys4(est, l0, d);
-        uint32_t gt = 0, eq = 0;                                     // bit z: key z is above / at the threshold
-#pragma unroll
-        for (int z = 0; z < 4; ++z) {
-            const uint32_t key = mag_key(q.v[z]);
-            const bool have = (q.have >> z) & 1u;
-            gt |= (have && key > tau) ? (1u << z) : 0u;
-            eq |= (have && key == tau) ? (1u << z) : 0u;
-        }
-        uint32_t eq_before, eq_total;
-        wave_prefix3((uint32_t)__popc(eq), below, &eq_before, &eq_total);
-        uint32_t take = gt;
-#pragma unroll
-        for (int z = 0; z < 4; ++z) {
-            const uint32_t rank = eqr + eq_before + (uint32_t)__popc(eq & ((1u << z) - 1u));
-            if (((eq >> z) & 1u) && rank < k_eq) take |= 1u << z;
-        }
-        uint32_t take_before, take_total;
-        wave_prefix3((uint32_t)__popc(take), below, &take_before, &take_total);
-#pragma unroll
-        for (int z = 0; z < 4; ++z) {
-            if ((take >> z) & 1u) {
-                const int64_t pos = (int64_t)out + take_before + __popc(take & ((1u << z) - 1u));
-                if (pos < k) {
-                    idx[pos] = (int32_t)(l0 + z);
-                    if (est_sel) est_sel[pos] = q.v[z];
-                }
-            }
-        }
-        out += take_total;
-        eqr += eq_total;
+        compact_keys4(load_keys4(est, l0, d), l0, tau, k_eq, below, out, eqr, k, idx, est_sel);
     }
 }
 
@@ -293,13 +334,15 @@ k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict
 // The whole selection in one workgroup of 1024 threads for len <= kSelSmallMax keys: the three histogram passes
 // with their digit picks, the counts per segment of kSelSmallSeg keys (one wavefront each), their prefixes, and
 // the ordered compaction.  Same arithmetic as the kernels above; replaces ten launches, which is most of the
-// step's time when the vector has only tens of thousands of coordinates.
+// step's time when the vector has only tens of thousands of coordinates.  (Its time is that of the LDS atomics of
+// the first pass, where most keys share a few top digits; keeping the keys in registers across the phases instead
+// of re-reading them from the L2 was tried and changes nothing.)
 __global__ void __launch_bounds__(1024)
 k_sel_small(const float *__restrict__ keys, int64_t len, uint32_t k, int32_t *__restrict__ idx,
             float *__restrict__ val_sel)
 {
     __shared__ uint32_t lh[kHistBins];
-    __shared__ uint32_t part[1024];
+    __shared__ uint32_t part[16];
     __shared__ uint32_t sh[2];                                       // prefix, k_rem after a pick
     __shared__ uint32_t seg_gt[16], seg_eq[16], seg_sel_base[16], seg_eq_base[16];
     const int t = threadIdx.x;
