@@ -68,7 +68,7 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
     "chunk-records": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=16,
                           scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0,
                           fuse_median=1, stage_interleave=1, acc_wide=2),
-    "chunk-records-worker-major": dict(tile_log2=13, win_log2=14, chunk_log2=11, acc_threads=1024, run_pad=32,
+    "chunk-records-worker-major": dict(tile_log2=13, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32,
                                        scatter_threads=512, sketch_path=2, estimate_path=0, fuse_head=0, stage_rows=2,
                                        fuse_median=1, stage_interleave=0, acc_wide=2),
     "accumulate-16-byte-loads-worker-major": dict(tile_log2=10, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=32,
@@ -209,6 +209,32 @@ def test_sketch_accumulate_keeps_subnormal_sums(sams, path, d, c):
         S = torch.empty((n, r, c), device="cuda")
         ctx.sketch_accumulate(dev(u), S)
         assert np.array_equal(host(S), want)
+
+
+@pytest.mark.parametrize("d,n,r,c,k", [(400_001, 1, 3, 150_001, 50),       # one worker, ragged last window, d not a multiple of 4
+                                       (250_000, 4, 5, 65_536, 100),       # two full windows
+                                       (131_072, 2, 16, 40_000, 10),       # sixteen rows, one partly filled window
+                                       (1_000_000, 3, 2, 1_000_003, 7)])   # 31 windows, long bins
+@pytest.mark.parametrize("layout", ["chunk-records", "chunk-records-worker-major"])
+def test_record_kernel_tables_bit_exact(sams, layout, d, n, r, c, k):
+    """The second pass through chunk records (values and codes in registers, chains by rank) on shapes chosen so that
+    most rows do use records: float inputs, tables equal to the sequential sum bit for bit."""
+    hp = inputs.hash_params(r, seed=21)
+    rng = np.random.default_rng(d + n)
+    u = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-5, 0, (n, d))).astype(np.float32)
+    o = Oracle("f32")
+    want = np.stack([o.sketch(u[i], hp, c) for i in range(n)])
+    for key, val in dict(PATHS[layout], fuse_head=0).items():
+        sams.sams_configure(key, val)
+    try:
+        with sams.Context(d, n, r, c, k, hp) as ctx:
+            assert bin(ctx.record_rows).count("1") >= r // 2, ctx.record_rows
+            S = torch.full((n, r, c), 3.0, device="cuda")
+            ctx.sketch_accumulate(dev(u), S)
+            assert np.array_equal(host(S), want)
+    finally:
+        for key, val in PATHS["default"].items():
+            sams.sams_configure(key, val)
 
 
 def test_rows_choose_between_chunk_records_and_meta_words_one_by_one(sams):
