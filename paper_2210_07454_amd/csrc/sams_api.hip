@@ -10,7 +10,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 1, 2};
+Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 0, 2};
 static std::mutex g_tun_mutex;      // sams_configure against the copy sams_create takes
 
 static const char *const kKernelNames[KID_COUNT] = {

@@ -951,87 +951,29 @@ k_bin_accumulate_q(const float *__restrict__ stg, const uint32_t *__restrict__ m
 
 // Variant reading chunk records instead of meta words (1024 threads, chunks of 4096 positions, windows of up to 2^15
 // buckets).  A thread owns four consecutive positions per chunk and keeps their values and codes in registers: one
-// 16-byte streaming load of the values, one 8-byte load of the codes (the records are shared by the n workers of a
-// (row, bin) through the L2); waves 0-1 also fetch the chunk's chain entries.  Per chunk: the positions that share
-// their bucket with another position of the chunk (about an eighth with 2^15 windows) put their values into a small
-// LDS array at their rank; after the one barrier every other position adds its value to its bucket, a plain
-// read-modify-write since nothing else touches that bucket before the next barrier, and thread e < 512 adds the
-// values of chain e to the chain's bucket in rank order, which is stream order.  The buckets of the chains and of
-// the single positions are disjoint, so the two need no barrier between them.  Same order of additions per bucket,
-// hence the same results, as k_bin_accumulate.
-typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
-
-// The chunk loop, instantiated per role of a wave (ENT: fetches chain entries; CHAINS: its threads process chains).
-// Separate copies of the loop rather than loads and stores under per-wave conditions: every load is then issued
-// unconditionally and in a fixed order, so that the compiler can wait for exactly the oldest one of the ring.
-template <bool ENT, bool CHAINS>
-__device__ __forceinline__ void acc_r_chunks(const vec4f *__restrict__ vsrc, int64_t vstride, const uint2 *__restrict__ csrc,
-                                             const vec4u *__restrict__ esrc, float *win, float *mv, uint32_t *ent,
-                                             int64_t nchunk)
-{
-    constexpr int kMv = kRecRanks + kRecPadRanks;
-    vec4f rv[kRecDepth];
-    uint2 rc[kRecDepth];
-    vec4u re[kRecDepth];
-    const int64_t last = nchunk - 1;
-#pragma unroll
-    for (int s = 0; s < kRecDepth; ++s) {
-        const int64_t qs = s < last ? s : last;
-        rv[s] = __builtin_nontemporal_load(vsrc + qs * vstride);
-        rc[s] = csrc[qs * (kRecWords / 2)];
-        if constexpr (ENT) re[s] = esrc[qs * (kRecWords / 4)];
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    for (int64_t q0 = 0; q0 < nchunk; q0 += kRecDepth) {
-#pragma unroll
-        for (int s = 0; s < kRecDepth; ++s) {
-            const int64_t q = q0 + s;
-            if (q < nchunk) {                                        // uniform over the workgroup
-                float *mvp = mv + (s & 1) * kMv;                      // q0 is even: the chunk's parity is that of s
-                uint32_t *entp = ent + (s & 1) * kRecChains;
-                const float vals[4] = {rv[s].x, rv[s].y, rv[s].z, rv[s].w};
-                const uint32_t codes[4] = {rc[s].x & 0xffffu, rc[s].x >> 16, rc[s].y & 0xffffu, rc[s].y >> 16};
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    if (codes[z] >= kCodeChain) mvp[codes[z] & kCodeRankMask] = vals[z];
-                if constexpr (ENT) *reinterpret_cast<vec4u *>(entp + 4 * threadIdx.x) = re[s];
-                __syncthreads();   // also orders the previous chunk's window updates before this chunk's
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-                    if (codes[z] < kCodeChain) win[codes[z]] = win[codes[z]] + vals[z];
-                if constexpr (CHAINS) {
-                    const uint32_t word = entp[threadIdx.x];
-                    const uint32_t cnt = word >> 25;
-                    if (cnt) {
-                        const uint32_t w = word & 0x7fffu;
-                        const float *mc = mvp + ((word >> 15) & (uint32_t)(kRecRanks - 1));
-                        float x = win[w];
-                        for (uint32_t o = 0; o < cnt; ++o) x = x + mc[o];
-                        win[w] = x;
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            const int64_t qn = (q + kRecDepth) < last ? (q + kRecDepth) : last;
-            rv[s] = __builtin_nontemporal_load(vsrc + qn * vstride);
-            rc[s] = csrc[qn * (kRecWords / 2)];
-            if constexpr (ENT) re[s] = esrc[qn * (kRecWords / 4)];
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-}
-
+// 16-byte streaming load of the values, one 8-byte load of the codes, and -- every thread pair (2e, 2e + 1) -- the
+// 4-byte entry of chain e (the records are shared by the n workers of a (row, bin) through the L2).  Per chunk: the
+// positions that share their bucket with another position of the chunk (about an eighth with 2^15 windows) put their
+// values into a small LDS array at their rank; after the one barrier every other position adds its value to its
+// bucket, a plain read-modify-write since nothing else touches that bucket before the next barrier, and thread 2e adds
+// the values of chain e to the chain's bucket in rank order, which is stream order.  The buckets of the chains and of
+// the single positions are disjoint, so the two need no barrier between them.  Every wave does the same work (a
+// version in which the first two waves fetched the entries into LDS and the first eight processed the chains ran
+// at the same speed with three copies of the loop).  Same order of additions per bucket, hence the same results,
+// as k_bin_accumulate.
+// Every load of the ring is issued unconditionally and in a fixed order, straight into the registers the loop
+// carries, so that the compiler waits for exactly the oldest chunk.
 __global__ void __launch_bounds__(1024)
 k_bin_accumulate_r(const float *__restrict__ stg, const uint32_t *__restrict__ rec,
                    const uint32_t *__restrict__ binbase, float *__restrict__ S, int32_t n, RowGroup rg, RowSel sel,
                    int64_t c, int win_log2, int64_t nbins, int64_t rowlen)
 {
     constexpr int CH = kRecChunk;
+    constexpr int kMv = kRecRanks + kRecPadRanks;
     extern __shared__ float lds[];
     const int W = 1 << win_log2;
     float *win = lds;
-    float *mv = lds + W;                                             // [2][kRecRanks + kRecPadRanks] values of chain positions
-    uint32_t *ent = reinterpret_cast<uint32_t *>(mv + 2 * (kRecRanks + kRecPadRanks));   // [2][kRecChains]
+    float *mv = lds + W;                                             // [2][kMv] values of chain positions, by chunk parity
     const int64_t id = blockIdx.x;
     const int64_t slot = id / kNumXcd;
     const int64_t group = (id % kNumXcd) + kNumXcd * (slot / n);     // (row, bin) index
@@ -1044,20 +986,61 @@ k_bin_accumulate_r(const float *__restrict__ stg, const uint32_t *__restrict__ r
     for (int t = threadIdx.x; t < W; t += 1024) win[t] = 0.f;
     if (nchunk > 0) {                                                // uniform over the workgroup
         const uint32_t t = threadIdx.x;
-        // this thread's four positions of chunk q: values at vsrc[q * vstride], codes at csrc[q * (kRecWords / 2)]
+        // this thread's four positions of chunk q: values at vsrc[q * vstride], codes at csrc[q * (kRecWords / 2)],
+        // the entry of chain t / 2 at esrc[q * kRecWords]
         const vec4f *vsrc = reinterpret_cast<const vec4f *>(stg + stage_row(rg, n, rowlen, i, jj) +
                                                             stage_pos(rg, n, (uint32_t)b0) + stage_pos(rg, n, 4 * t));
         const int64_t vstride = (int64_t)(CH / 4) * (rg.ilv ? n : 1);
         const uint32_t *r0 = rec + ((int64_t)j * (rowlen / CH) + b0 / CH) * kRecWords;
         const uint2 *csrc = reinterpret_cast<const uint2 *>(r0) + t;
-        const vec4u *esrc = reinterpret_cast<const vec4u *>(r0 + kRecCodeWords) + (t & (kRecChains / 4 - 1));
-        const int wave = __builtin_amdgcn_readfirstlane((int)(t >> 6));   // uniform, kept in a scalar register
-        if (wave < kRecChains / 4 / kWave)
-            acc_r_chunks<true, true>(vsrc, vstride, csrc, esrc, win, mv, ent, nchunk);
-        else if (wave < kRecChains / kWave)
-            acc_r_chunks<false, true>(vsrc, vstride, csrc, esrc, win, mv, ent, nchunk);
-        else
-            acc_r_chunks<false, false>(vsrc, vstride, csrc, esrc, win, mv, ent, nchunk);
+        const uint32_t *esrc = r0 + kRecCodeWords + (t >> 1);
+        const bool chain_thread = (t & 1u) == 0;
+        vec4f rv[kRecDepth];
+        uint2 rc[kRecDepth];
+        uint32_t re[kRecDepth];
+        const int64_t last = nchunk - 1;
+#pragma unroll
+        for (int s = 0; s < kRecDepth; ++s) {
+            const int64_t qs = s < last ? s : last;
+            rv[s] = __builtin_nontemporal_load(vsrc + qs * vstride);
+            rc[s] = csrc[qs * (kRecWords / 2)];
+            re[s] = esrc[qs * kRecWords];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (int64_t q0 = 0; q0 < nchunk; q0 += kRecDepth) {
+#pragma unroll
+            for (int s = 0; s < kRecDepth; ++s) {
+                const int64_t q = q0 + s;
+                if (q < nchunk) {                                    // uniform over the workgroup
+                    float *mvp = mv + (s & 1) * kMv;                  // q0 is even: the chunk's parity is that of s
+                    const float vals[4] = {rv[s].x, rv[s].y, rv[s].z, rv[s].w};
+                    const uint32_t codes[4] = {rc[s].x & 0xffffu, rc[s].x >> 16, rc[s].y & 0xffffu, rc[s].y >> 16};
+#pragma unroll
+                    for (int z = 0; z < 4; ++z)
+                        if (codes[z] >= kCodeChain) mvp[codes[z] & kCodeRankMask] = vals[z];
+                    __syncthreads();   // also orders the previous chunk's window updates before this chunk's
+#pragma unroll
+                    for (int z = 0; z < 4; ++z)
+                        if (codes[z] < kCodeChain) win[codes[z]] = win[codes[z]] + vals[z];
+                    const uint32_t word = re[s];
+                    const uint32_t cnt = chain_thread ? word >> 25 : 0u;
+                    if (cnt) {
+                        const uint32_t w = word & 0x7fffu;
+                        const float *mc = mvp + ((word >> 15) & (uint32_t)(kRecRanks - 1));
+                        float x = win[w];
+                        for (uint32_t o = 0; o < cnt; ++o) x = x + mc[o];
+                        win[w] = x;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // (refilling the registers before the chunk is processed instead of after it changes nothing)
+                const int64_t qn = (q + kRecDepth) < last ? (q + kRecDepth) : last;
+                rv[s] = __builtin_nontemporal_load(vsrc + qn * vstride);
+                rc[s] = csrc[qn * (kRecWords / 2)];
+                re[s] = esrc[qn * kRecWords];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     }
     __syncthreads();
     const int64_t base = bin << win_log2;
@@ -1432,7 +1415,7 @@ static int dispatch_acc(sams_ctx *ctx, float *S_workers, RowGroup rg, bool set_a
     if (!set_attr && with_rec.cnt > 0) {
         const int64_t groups = (int64_t)with_rec.cnt * pl.nbins;
         const int64_t gpad = (groups + kNumXcd - 1) / kNumXcd * kNumXcd;
-        const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * (kRecRanks + kRecPadRanks) * 4 + (size_t)2 * kRecChains * 4;
+        const size_t lds = ((size_t)4 << pl.win_log2) + (size_t)2 * (kRecRanks + kRecPadRanks) * 4;
         ProfScope ps(ctx, KID_BIN_ACCUMULATE);
         hipLaunchKernelGGL(k_bin_accumulate_r, dim3((unsigned)(gpad * ctx->n)), dim3(1024), lds, ctx->stream, pl.stg,
                            pl.rec, pl.binbase, S_workers, ctx->n, rg, with_rec, ctx->c, pl.win_log2, pl.nbins, pl.rowlen);

@@ -27,7 +27,7 @@ def sams():
 
 PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must not depend on it
     "default": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
-                    sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=1, acc_wide=2),
+                    sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=2),
     "worker-major-staging": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
                                  sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1,
                                  stage_interleave=0, acc_wide=0),

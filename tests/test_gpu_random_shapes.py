@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
 DEFAULTS = dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
-                sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=1, acc_wide=2)
+                sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=2)
 
 
 def dev(a):
