@@ -128,6 +128,19 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
         ctx->scratch_bytes += a.bytes;
     }
     void *static_scratch = nullptr;
+    if (ctx->tun.fuse_head == 2 && ctx->tun.sketch_path != 1) {      // the per-worker fused head compacts g on I_{t-1}
+        struct { void **p; int64_t bytes; } extra[] = {{(void **)&ctx->wordrank, words * 4}, {(void **)&ctx->gsel, (int64_t)n * k * 4}};
+        for (auto &a : extra) {
+            hipError_t e = hipMalloc(a.p, (size_t)a.bytes);
+            if (e != hipSuccess) {
+                g_last_hip_error = (int)e;
+                (void)hipGetLastError();
+                sams_destroy(ctx);
+                return SAMS_ENOMEM;
+            }
+            ctx->scratch_bytes += a.bytes;
+        }
+    }
     int rc = static_scratch_ptr(&static_scratch);                    // resolved here so that topk_refine_static never has to
     if (rc == SAMS_OK) rc = enqueue_fill_u32(ctx, ctx->bitmap, words, 0u);
     if (rc == SAMS_OK && ctx->tun.sketch_path != 1) rc = plan_create(ctx, ctx->tun);
@@ -145,7 +158,7 @@ int sams_destroy(sams_ctx *ctx)
     int rc = SAMS_OK;
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; }
-    void *ptrs[] = {ctx->est, ctx->bitmap, ctx->hist, ctx->sel, ctx->cnt, ctx->base};
+    void *ptrs[] = {ctx->est, ctx->bitmap, ctx->wordrank, ctx->gsel, ctx->hist, ctx->sel, ctx->cnt, ctx->base};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     plan_destroy(ctx);

@@ -124,6 +124,9 @@ struct sams_ctx {
     // scratch (device)
     float *est;              // [d]
     uint32_t *bitmap;        // [ceil(d/32)]  bit l set <=> l in the most recent index set
+    uint32_t *wordrank;      // [ceil(d/32)]  for a bitmap word with a bit set: the rank (position in idx) of its first set bit;
+                             //               with gsel, only where the head is fused per worker (fuse_head = 2), else null
+    float *gsel;             // [n][k]        g of every worker at the coordinates of the most recent index set, by rank
     uint32_t *hist;          // [kHistBins]
     sams::SelState *sel;     // [1]
     uint32_t *cnt;           // [2][ntile]  per-wavefront-tile counts: greater, equal
@@ -246,6 +249,9 @@ int enqueue_row_estimates_planned(sams_ctx *ctx, const float *S_mean, float *row
 int enqueue_estimates_planned_fused(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, bool *done,
                                     uint32_t *hist);   // hist: null, or where to add the first-digit histogram of |est|
 bool head_can_fuse(const sams_ctx *ctx);
+// wordrank and gsel exist for this context (sams_create decides): the per-worker fused head then leaves the
+// gradients of the selected coordinates in gsel and the second moments on I_{t-1} need no gathers
+bool head_compacts_g(const sams_ctx *ctx);
 int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, float *v, float *vhat,
                          float beta1, float beta2, float rho, bool pa,   // pa: v, vhat are [n][d] (Alg. 1)
                          const int32_t *idx_prev, int64_t k_prev);       // I_{t-1}, as handed to the tail

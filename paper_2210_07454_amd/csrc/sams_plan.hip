@@ -59,7 +59,7 @@ constexpr int kRecPadRanks = 256;              // dummy ranks of the padding pos
 constexpr int kRecMaxChain = 127;              // positions one chain may have
 constexpr int kRecWords = kRecCodeWords + kRecChains;
 constexpr uint32_t kCodeChain = 0x8000u, kCodeRankMask = 0x7ffu;
-constexpr int kRecDepth = 4;                   // chunks in flight per workgroup of k_bin_accumulate_r (even)
+constexpr int kRecDepth = 6;                   // chunks in flight per workgroup of k_bin_accumulate_r (even; 4 and 8 measured 3-5 % slower)
 
 // streaming accesses: data touched once per step should not push the shared metadata out of L2.
 // One 16-byte nontemporal instruction each (the pointers are 16-byte aligned, as float4 requires).
@@ -497,6 +497,9 @@ struct HeadArgs {
     float *m, *e, *v, *vhat;
     const uint32_t *bitmap;
     float beta1, omb1, beta2, omb2, rho;
+    const uint32_t *wordrank;   // with gsel: where the per-worker head leaves g on I_{t-1} (null: it does not)
+    float *gsel;
+    int64_t k_prev;
 };
 
 // PA: the head of Alg. 1 instead (every worker keeps its own v, vhat [n][d]; u = m / sqrt(vhat) + rho e).
@@ -633,13 +636,18 @@ k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t 
     if (slot / n >= per || tile >= ntile) return;
     const int64_t l0 = tile << tile_log2;
     const int64_t wbase = (int64_t)i * d + l0;
+    float4 gkeep[kFusedIters];                                       // g and the bitmap word of the positions with a
+    uint32_t wkeep[kFusedIters];                                     // member of I_{t-1}, for the compaction below
+#pragma unroll
+    for (int it = 0; it < kFusedIters; ++it) { gkeep[it] = make_float4(0.f, 0.f, 0.f, 0.f); wkeep[it] = 0u; }
 #pragma unroll
     for (int it = 0; it < kFusedIters; ++it) {
         const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
         if (p < L) {
             float uv[4] = {0.f, 0.f, 0.f, 0.f};
             if (l0 + p < d) {
-                const uint32_t selbits = (ha.bitmap[(l0 + p) >> 5] >> ((l0 + p) & 31)) & 0xFu;
+                const uint32_t bword = ha.bitmap[(l0 + p) >> 5];
+                const uint32_t selbits = (bword >> ((l0 + p) & 31)) & 0xFu;
                 const float4 a = load_stream(reinterpret_cast<const float4 *>(ha.g + wbase + p));
                 const float4 b = load_stream(reinterpret_cast<const float4 *>(ha.m + wbase + p));
                 const float4 cc = load_stream(reinterpret_cast<const float4 *>(ha.e + wbase + p));
@@ -669,6 +677,8 @@ k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t 
                         mo[t] = mm;
                         uv[t] = mm + (ha.rho * ein);
                     }
+                    gkeep[it] = a;
+                    wkeep[it] = selbits ? bword : 0u;
                     if (i == 0) {                                    // the decay of v, once per coordinate
                         const float4 vin = *reinterpret_cast<const float4 *>(ha.v + l0 + p);
                         const float4 hin = *reinterpret_cast<const float4 *>(ha.vhat + l0 + p);
@@ -687,6 +697,28 @@ k_head_scatter_w(HeadArgs ha, const uint16_t *__restrict__ srcp, const uint32_t 
                 store_stream(reinterpret_cast<float4 *>(ha.e + wbase + p), make_float4(uv[0], uv[1], uv[2], uv[3]));
             }
             *reinterpret_cast<float4 *>(tilebuf + p) = make_float4(uv[0], uv[1], uv[2], uv[3]);
+        }
+    }
+    if constexpr (!PA) {
+        // g of this worker at the coordinates of I_{t-1}, at their rank in the index set: the rank of the word's
+        // first member plus the members of the word below the coordinate.  Kept out of the streaming loop above,
+        // whose loads a wait for the rank would hold up.
+        if (ha.gsel) {
+#pragma unroll
+            for (int it = 0; it < kFusedIters; ++it) {
+                const uint32_t selbits4 = (wkeep[it] >> ((uint32_t)((it * kFusedThreads + (int)threadIdx.x) * 4) & 31u)) & 0xFu;
+                if (selbits4) {
+                    const int p = (it * kFusedThreads + (int)threadIdx.x) * 4;
+                    const uint32_t r0 = ha.wordrank[(l0 + p) >> 5];
+                    const float gv[4] = {gkeep[it].x, gkeep[it].y, gkeep[it].z, gkeep[it].w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if ((selbits4 >> t) & 1u) {
+                            const uint32_t below = wkeep[it] & ((1u << (((uint32_t)p & 31u) + t)) - 1u);
+                            ha.gsel[(int64_t)i * ha.k_prev + r0 + __popc(below)] = gv[t];
+                        }
+                }
+            }
         }
     }
     __syncthreads();
@@ -756,6 +788,22 @@ k_head_sparse_v_wide(const float *__restrict__ g, const int32_t *__restrict__ id
         v[l] = vv;
         if (vv > vhat[l]) vhat[l] = vv;
     }
+}
+
+// the same from the gradients the per-worker head has left in gsel[n][k_sel] (by rank in the index set): no gathers
+__global__ void __launch_bounds__(256)
+k_head_sparse_v_sel(const float *__restrict__ gsel, const int32_t *__restrict__ idx, int64_t k_sel, int32_t n, float omb2,
+                    float *__restrict__ v, float *__restrict__ vhat)
+{
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= k_sel) return;
+    const int64_t l = idx[q];
+    float gs = gsel[q];
+    for (int32_t i = 1; i < n; ++i) gs = (gs + gsel[(int64_t)i * k_sel + q]);
+    const float h = (gs / (float)n);
+    const float vv = (v[l] + (omb2 * (h * h)));
+    v[l] = vv;
+    if (vv > vhat[l]) vhat[l] = vv;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1668,6 +1716,8 @@ void plan_destroy(sams_ctx *ctx)
     pl.stg = pl.rowest = nullptr;
 }
 
+bool head_compacts_g(const sams_ctx *ctx) { return ctx->wordrank != nullptr && ctx->gsel != nullptr; }
+
 bool head_can_fuse(const sams_ctx *ctx)
 {
     return ctx->tun.fuse_head && ctx->plan.mode == PLAN_BINNED && (ctx->d & 3) == 0 && ctx->plan.tile_log2 <= 14;
@@ -1679,7 +1729,9 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
     Plan &pl = ctx->plan;
     const int64_t L = (int64_t)1 << pl.tile_log2;
     const int64_t per = (pl.ntile + kNumXcd - 1) / kNumXcd;
-    HeadArgs ha = {g, m, e_u, v, vhat, ctx->bitmap, beta1, 1.0f - beta1, beta2, 1.0f - beta2, rho};
+    const bool compact = head_compacts_g(ctx) && !pa && k_prev > 0;
+    HeadArgs ha = {g, m, e_u, v, vhat, ctx->bitmap, beta1, 1.0f - beta1, beta2, 1.0f - beta2, rho,
+                   compact ? ctx->wordrank : nullptr, compact ? ctx->gsel : nullptr, k_prev};
     {
         ProfScope ps(ctx, KID_HEAD_SCATTER);
         const dim3 grid((unsigned)(per * kNumXcd));
@@ -1703,7 +1755,10 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                                pl.srcp, pl.dst16, pl.pbase, pl.stg, ctx->n, rg, ctx->d, pl.tile_log2, pl.ntile,
                                pl.rowlen, pl.grp_log2);
     }
-    if (ctx->tun.fuse_head == 2 && !pa && k_prev > 0) {
+    if (compact) {
+        SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_sel, (unsigned)((k_prev + 255) / 256), 256, ctx->gsel, idx_prev,
+                    k_prev, ctx->n, 1.0f - beta2, v, vhat);
+    } else if (ctx->tun.fuse_head == 2 && !pa && k_prev > 0) {
         if (ctx->n >= kWideMinWorkers)
             SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_wide, (unsigned)((k_prev + kWideCoords - 1) / kWideCoords),
                         256, g, idx_prev, k_prev, ctx->n, ctx->d, 1.0f - beta2, v, vhat);

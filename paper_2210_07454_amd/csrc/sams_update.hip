@@ -12,15 +12,17 @@ namespace sams {
 // ------------------------------------------------------------------------------------------
 // stage 5: tail (finish iteration t) and head (start iteration t+1) of Alg. 2
 // ------------------------------------------------------------------------------------------
-// x[idx[q]] -= lr * delta[q]; mark idx[q] in the bitmap (I_t for the next head)
+// x[idx[q]] -= lr * delta[q]; mark idx[q] in the bitmap (I_t for the next head).  wordrank != null: idx is ascending
+// (as amsgrad_ef_update requires), so the rank of the first coordinate of every bitmap word that has one is its q
 __global__ void k_tail_x(const int32_t *__restrict__ idx, const float *__restrict__ delta, int64_t k,
-                         float lr, float *__restrict__ x, uint32_t *__restrict__ bitmap)
+                         float lr, float *__restrict__ x, uint32_t *__restrict__ bitmap, uint32_t *__restrict__ wordrank)
 {
     int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
     if (q >= k) return;
     uint32_t l = (uint32_t)idx[q];
     x[l] = (x[l] - (lr * delta[q]));
     atomicOr(&bitmap[l >> 5], 1u << (l & 31));
+    if (wordrank && (q == 0 || ((uint32_t)idx[q - 1] >> 5) != (l >> 5))) wordrank[l >> 5] = (uint32_t)q;
 }
 
 // e[i][idx[q]] = 0 (only needed when no head follows; otherwise the head reads the bitmap)
@@ -265,7 +267,7 @@ int enqueue_tail(sams_ctx *ctx, float *e_u, float *x, const int32_t *idx, const 
     SAMS_TRY(enqueue_fill_u32(ctx, ctx->bitmap, words, 0u));
     if (k_sel > 0) {
         SAMS_LAUNCH(ctx, KID_TAIL_X, k_tail_x, grid_for(k_sel, 256), 256, idx, delta, k_sel, lr, x,
-                    ctx->bitmap);
+                    ctx->bitmap, ctx->wordrank);
         if (zero_e)
             SAMS_LAUNCH(ctx, KID_TAIL_ZERO_E, k_tail_zero_e, grid_for(k_sel, 256), 256, idx, k_sel,
                         ctx->n, ctx->d, e_u);
