@@ -165,7 +165,7 @@ def test_full_size_variants_parameter_averaging_and_second_round(wl, P):
 @pytest.mark.timeout(1500)
 def test_stress_size_second_iteration_sampled(capfd):
     """C5 (d = 1.3 G): the binned path with two sketch rows staged at a time so that state, plan and staging fit
-    in HBM together (the staging then also holds the looked-up values of all five rows, so the median stays fused).  Outputs the oracle can afford are checked in full (two whole (worker, row) tables, the mean
+    in HBM together (the staging then also holds the looked-up values of all five rows, so the median stays fused).  Outputs the oracle can afford are checked in full (a whole (worker, row) table, the mean
     table, the gathered values), the rest on coordinate ranges at both ends of the vector, and the index set
     through the properties that define it."""
     from paper_2210_07454_amd import sams
@@ -186,7 +186,7 @@ def test_stress_size_second_iteration_sampled(capfd):
         gs = inputs.GradientStream(w, device="cuda")
         hp = inputs.hash_params(r, seed=w.seed)
         o = Oracle("f32")
-        edge = 16_000_000
+        edge = 8_000_000
         ranges = [(0, edge), (d - edge, d)]
         with sams.Context(d, n, r, c, k, hp) as ctx:
             say(f"context ready, scratch {ctx.scratch_bytes / 2**30:.1f} GiB")
@@ -219,9 +219,9 @@ def test_stress_size_second_iteration_sampled(capfd):
                     assert np.array_equal(host(t[a:z].contiguous()), st[key]), (key, a)
             say("dense update checked on both ends")
             del g, pre
-            # stage 1: two whole (worker, row) tables, bit for bit
+            # stage 1: one whole (worker, row) table, bit for bit (every coordinate of the worker's vector enters it)
             ctx.sketch_accumulate(b.e_u, b.S_workers)
-            for i, j in ((0, 0), (n - 1, r - 1)):
+            for i, j in ((n - 1, r - 1),):
                 want = o.sketch(host(b.e_u[i]), hp[j:j + 1], c)[0]
                 assert np.array_equal(host(b.S_workers[i, j]), want), ("sketch", i, j)
                 say(f"table of worker {i}, row {j} checked")

@@ -364,6 +364,57 @@ def test_amsgrad_ef_update_head_and_tail_bit_exact(sams, path, d, n, r, c, k):
             assert np.array_equal(host(got), want)
 
 
+INDEX_SETS = {
+    "every-coordinate": lambda d, rng: np.arange(d),
+    "every-other": lambda d, rng: np.arange(0, d, 2),
+    "whole-bitmap-words": lambda d, rng: np.concatenate([np.arange(w * 32, w * 32 + 32) for w in (0, 7, 511, 512, d // 32 - 1)]),
+    "tile-edges": lambda d, rng: np.unique(np.concatenate([[0, d - 1], np.arange(1, d >> 10) * 1024 - 1, np.arange(1, d >> 10) * 1024])),
+    "one-coordinate": lambda d, rng: np.array([d // 3]),
+    "dense-random": lambda d, rng: np.sort(rng.choice(d, d // 3, replace=False)),
+    "one-tile-only": lambda d, rng: 16384 + np.sort(rng.choice(16384, 900, replace=False)),
+}
+
+
+@pytest.mark.parametrize("shape", list(INDEX_SETS))
+@pytest.mark.parametrize("d,tile_log2", [(50_000, 0), (70_004, 10)], ids=["tiles-2^14", "tiles-2^10-ragged-d"])
+def test_head_per_worker_on_dense_and_clustered_index_sets(sams, shape, d, tile_log2):
+    """Sec. II-C, Alg. 2: v_t = beta2 v_{t-1} + (1 - beta2) h_t^2 with h_t the workers' mean gradient on I_{t-1}, zero elsewhere.
+    The head that runs one workgroup per (tile, worker) takes h_t from the gradients it has compacted by their rank in the index set;
+    index sets with full bitmap words, neighbours across word and tile borders, a single member and empty tiles."""
+    n, r, c = 3, 3, 5000
+    rng = np.random.default_rng(len(shape) * 1000 + d)
+    o = Oracle("f32")
+    b1, b2, lr = 0.9, 0.99, 1e-3
+    f = lambda *s: (rng.standard_normal(s) * 10.0 ** rng.uniform(-4, 0, s)).astype(np.float32)
+    idx = INDEX_SETS[shape](d, rng).astype(np.int32)
+    k = len(idx)
+    g1, g2, m, e, x, delta = f(n, d), f(n, d), f(n, d), f(n, d), f(d), f(k)
+    v = (10.0 ** rng.uniform(-8, -2, d)).astype(np.float32)
+    vhat = np.maximum(v, (10.0 ** rng.uniform(-8, -2, d)).astype(np.float32))
+    for key, val in dict(PATHS["default"], fuse_head=2, sketch_path=2, tile_log2=tile_log2).items():
+        sams.sams_configure(key, val)
+    try:
+        with sams.Context(d, n, r, c, k, inputs.hash_params(r)) as ctx:
+            md, ed, vd, vhd, xd = dev(m), dev(e), dev(v), dev(vhat), dev(x)
+            ctx.amsgrad_ef_update(dev(g1), md, ed, vd, vhd, xd, None, None, 0, b1, b2, lr)
+            o.head(g1, m, e, v, vhat, None, b1, b2)
+            for _ in range(2):                                  # twice: the second head reads what the first tail of the pair left
+                ctx.amsgrad_ef_update(dev(g2), md, ed, vd, vhd, xd, dev(idx), dev(delta), k, b1, b2, lr)
+                o.tail(e, x, idx, delta, lr)
+                mask = np.zeros(d, np.uint8)
+                mask[idx] = 1
+                o.head(g2, m, e, v, vhat, mask, b1, b2)
+                for name, got, want in (("m", md, m), ("e", ed, e), ("v", vd, v), ("vhat", vhd, vhat), ("x", xd, x)):
+                    assert np.array_equal(host(got), want), name
+                g2 = f(n, d)
+            S = torch.empty(n, r, c, device="cuda")
+            ctx.sketch_accumulate(ed, S)                        # the staged copy the head left is the sketch of u
+            assert np.array_equal(host(S), np.stack([o.sketch(e[i], inputs.hash_params(r), c) for i in range(n)]))
+    finally:
+        for key, val in PATHS["default"].items():
+            sams.sams_configure(key, val)
+
+
 @pytest.mark.parametrize("k_in,k_out", [(1, 1), (64, 64), (1000, 37), (50_000, 12_500), (400_000, 50_000)])
 def test_topk_refine_bit_exact_with_ties(sams, k_in, k_out):
     d = 3_000_000
