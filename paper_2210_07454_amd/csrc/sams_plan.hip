@@ -806,6 +806,28 @@ k_head_sparse_v_sel(const float *__restrict__ gsel, const int32_t *__restrict__ 
     if (vv > vhat[l]) vhat[l] = vv;
 }
 
+// ... with 32 lanes per coordinate for many workers
+__global__ void __launch_bounds__(256)
+k_head_sparse_v_sel_wide(const float *__restrict__ gsel, const int32_t *__restrict__ idx, int64_t k_sel, int32_t n,
+                         float omb2, float *__restrict__ v, float *__restrict__ vhat)
+{
+    __shared__ float vals[kWideCoords * kMaxWorkers];
+    const int ql = threadIdx.x >> 5, wl = threadIdx.x & 31;
+    const int64_t q = blockIdx.x * (int64_t)kWideCoords + ql;
+    if (q < k_sel)
+        for (int32_t i = wl; i < n; i += 32) vals[ql * n + i] = gsel[(int64_t)i * k_sel + q];
+    __syncthreads();
+    if (q < k_sel && wl == 0) {
+        const int64_t l = idx[q];
+        float gs = vals[ql * n];
+        for (int32_t i = 1; i < n; ++i) gs = (gs + vals[ql * n + i]);
+        const float h = (gs / (float)n);
+        const float vv = (v[l] + (omb2 * (h * h)));
+        v[l] = vv;
+        if (vv > vhat[l]) vhat[l] = vv;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // pass 2: per (worker, row, bin), add the bin's stream into an LDS window, chunk by chunk
 // ------------------------------------------------------------------------------------------
@@ -1756,8 +1778,12 @@ int enqueue_head_scatter(sams_ctx *ctx, const float *g, float *m, float *e_u, fl
                                pl.rowlen, pl.grp_log2);
     }
     if (compact) {
-        SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_sel, (unsigned)((k_prev + 255) / 256), 256, ctx->gsel, idx_prev,
-                    k_prev, ctx->n, 1.0f - beta2, v, vhat);
+        if (ctx->n >= kWideMinWorkers)
+            SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_sel_wide, (unsigned)((k_prev + kWideCoords - 1) / kWideCoords),
+                        256, ctx->gsel, idx_prev, k_prev, ctx->n, 1.0f - beta2, v, vhat);
+        else
+            SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_sel, (unsigned)((k_prev + 255) / 256), 256, ctx->gsel, idx_prev,
+                        k_prev, ctx->n, 1.0f - beta2, v, vhat);
     } else if (ctx->tun.fuse_head == 2 && !pa && k_prev > 0) {
         if (ctx->n >= kWideMinWorkers)
             SAMS_LAUNCH(ctx, KID_HEAD_SPARSE_V, k_head_sparse_v_wide, (unsigned)((k_prev + kWideCoords - 1) / kWideCoords),
