@@ -1534,6 +1534,12 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
         while (pl.win_log2 < 15 && ((int64_t)1 << pl.win_log2) < ctx->c &&
                (((int64_t)1 << pl.tile_log2) << pl.win_log2) / ctx->c < 64)
             ++pl.win_log2;                                           // but keep runs of at least 64 positions
+        // a small table under a short vector: nothing there is bound by bandwidth, and one workgroup per (worker, row)
+        // would walk the whole vector chunk after chunk; smaller windows (down to 2^7 buckets) share that walk out
+        if (ctx->c <= ((int64_t)1 << pl.win_log2) && ctx->d <= kOrderedSingleBinMaxD)
+            while (pl.win_log2 > 7 &&
+                   (int64_t)ctx->n * ctx->r * ((ctx->c + ((int64_t)1 << pl.win_log2) - 1) >> pl.win_log2) < 1024)
+                --pl.win_log2;
     }
     // a 32K window leaves room for one workgroup per unit: 1024 threads, 2048-position chunks; smaller
     // windows run two or more 512-thread workgroups per unit with 1024-position chunks
