@@ -280,16 +280,28 @@ __device__ __forceinline__ void compact_keys4(const Keys4 &q, int64_t l0, uint32
         gt |= (have && key > tau) ? (1u << z) : 0u;
         eq |= (have && key == tau) ? (1u << z) : 0u;
     }
-    uint32_t eq_before, eq_total;
-    wave_prefix3((uint32_t)__popc(eq), below, &eq_before, &eq_total);
+    // Most sweeps hold no key at the threshold and at most one selected key per lane: both prefixes then come from
+    // one ballot instead of three (the branches are uniform over the wavefront).
     uint32_t take = gt;
+    if (__ballot(eq != 0u) != 0) {
+        uint32_t eq_before, eq_total;
+        wave_prefix3((uint32_t)__popc(eq), below, &eq_before, &eq_total);
 #pragma unroll
-    for (int z = 0; z < 4; ++z) {
-        const uint32_t rank = eqr + eq_before + (uint32_t)__popc(eq & ((1u << z) - 1u));
-        if (((eq >> z) & 1u) && rank < k_eq) take |= 1u << z;
+        for (int z = 0; z < 4; ++z) {
+            const uint32_t rank = eqr + eq_before + (uint32_t)__popc(eq & ((1u << z) - 1u));
+            if (((eq >> z) & 1u) && rank < k_eq) take |= 1u << z;
+        }
+        eqr += eq_total;
     }
+    const uint64_t any = __ballot(take != 0u);
+    if (any == 0) return;
     uint32_t take_before, take_total;
-    wave_prefix3((uint32_t)__popc(take), below, &take_before, &take_total);
+    if (__ballot((take & (take - 1u)) != 0u) == 0) {                 // no lane selects two of its keys
+        take_before = (uint32_t)__popcll(any & below);
+        take_total = (uint32_t)__popcll(any);
+    } else {
+        wave_prefix3((uint32_t)__popc(take), below, &take_before, &take_total);
+    }
 #pragma unroll
     for (int z = 0; z < 4; ++z) {
         if ((take >> z) & 1u) {
@@ -301,7 +313,6 @@ __device__ __forceinline__ void compact_keys4(const Keys4 &q, int64_t l0, uint32
         }
     }
     out += take_total;
-    eqr += eq_total;
 }
 
 // one wavefront walks the keys [base, base + span) in index order and writes the selected ones at their rank;
