@@ -149,3 +149,31 @@ def test_random_shapes_and_launch_configurations(block, capfd):
             sams.sams_configure(key, val)
     say(f"block {block}: {ran} of 25 samples ran")
     assert ran >= 12                                  # most samples are configurations the library accepts
+
+
+LIMIT_SHAPES = {
+    "most-workers-most-rows": (2048, 1024, 16, 300, 64),
+    "most-workers-one-bucket": (4, 1024, 1, 1, 4),
+    "one-coordinate": (1, 1, 1, 1, 1),
+    "every-coordinate-selected-many-workers": (1000, 100, 5, 50, 1000),
+    "one-worker-table-larger-than-the-vector": (3000, 1, 16, 70_000, 17),
+}
+
+
+@pytest.mark.parametrize("fuse_head", [0, 2], ids=["separate-head", "fused-head-per-worker"])
+@pytest.mark.parametrize("name", list(LIMIT_SHAPES))
+def test_shapes_at_the_documented_limits(name, fuse_head, capfd):
+    """The largest worker and row counts sams_create accepts (n = 1024, r = 16), the smallest of everything, k = d,
+    and a table with more buckets than the vector has coordinates: one iteration and the head of the next, bit for bit."""
+    from paper_2210_07454_amd import sams
+    sams.load()
+    tun = dict(DEFAULTS, fuse_head=fuse_head, sketch_path=2 if fuse_head else 0)
+    try:
+        for key, val in tun.items():
+            sams.sams_configure(key, val)
+        with capfd.disabled():
+            print(f"[limits] {name}: d,n,r,c,k={LIMIT_SHAPES[name]} fuse_head={fuse_head}", flush=True)
+        assert one_iteration(sams, LIMIT_SHAPES[name], seed=len(name))
+    finally:
+        for key, val in DEFAULTS.items():
+            sams.sams_configure(key, val)
