@@ -112,8 +112,9 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *   "fuse_median" 1 (default) or 0: with 1 the plan-driven recovery keeps the row estimates in registers
  *                 (needs r <= 6 with tiles of 2^14, r <= 12 with 2^13, any r with 2^12 or less); with 0
  *                 they go through a [r][d] scratch array
- *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards;
- *                 1: one gather per (row, coordinate) straight from the table
+ *   "estimate_path" 0 (default): stage 3 reads the mean table through the same plan, run backwards, unless the
+ *                 table is at most 1 MiB and d <= 2^22 (then as with 1: such a table stays in cache);
+ *                 1: one gather per (row, coordinate) straight from the table; 2: through the plan whenever there is one
  *   "sketch_path" 0 (default): the binned, order-preserving path whenever c exceeds one LDS window, and
  *                 also for smaller tables while d <= 2^22 (one bin; one workgroup per (worker, row) walks the
  *                 vector); LDS atomics for small tables with larger d; 1: one global atomic add per term

@@ -193,7 +193,7 @@ int sams_configure(const char *key, int value)
         if (value != 256 && value != 512 && value != 1024) return SAMS_EINVAL;
         g_tun.scatter_threads = value;
     } else if (!strcmp(key, "estimate_path")) {
-        if (value < 0 || value > 1) return SAMS_EINVAL;
+        if (value < 0 || value > 2) return SAMS_EINVAL;
         g_tun.estimate_path = value;
     } else if (!strcmp(key, "fuse_head")) {
         if (value < 0 || value > 2) return SAMS_EINVAL;

@@ -94,7 +94,7 @@ struct Tunables {
     int acc_threads;   // workgroup size of the accumulate kernel
     int sketch_path;   // 0 = choose from c and d, 1 = global atomics, 2 = ordered (binned) always, 3 = LDS atomics when c fits a window
     int scatter_threads;  // workgroup size of the scatter kernel
-    int estimate_path;    // 0 = stage 3 through the plan when there is one, 1 = direct gathers from the table
+    int estimate_path;    // stage 3: 0 = through the plan when there is one, unless table and vector are small; 1 = direct gathers from the table; 2 = through the plan
     int fuse_head;        // 1, 2 = amsgrad_ef_update also stages u for the next sketch_accumulate (2: a workgroup per worker)
     int fuse_median;      // 1 = recovery keeps the row estimates in registers where the shape allows, 0 = through memory
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats

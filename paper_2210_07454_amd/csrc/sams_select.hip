@@ -419,12 +419,16 @@ k_sel_small(const float *__restrict__ keys, int64_t len, uint32_t k, int32_t *__
 
 // hist != null: the caller is about to select over est and has reset the selection state (enqueue_select_begin);
 // *hist_done tells whether the estimate kernel also took the histogram of the first radix digit
+constexpr int64_t kGatherEstimateMaxTableBytes = 1 << 20, kGatherEstimateMaxD = (int64_t)1 << 22;
 int enqueue_estimate(sams_ctx *ctx, const float *S_mean, const float *vhat, float *est, uint32_t *hist, bool *hist_done)
 {
     if (hist_done) *hist_done = false;
     const int block = 256;
     const int grid = grid_for(ctx->d, block);
-    if (ctx->plan.mode == PLAN_BINNED && ctx->tun.estimate_path == 0) {
+    // A small table under a short vector stays in every L2: r gathers per coordinate in one launch then beat the two
+    // launches of the plan-driven recovery (C1: 6 us against 23), which is made for tables far larger than any cache.
+    const bool small = (int64_t)ctx->r * ctx->c * 4 <= kGatherEstimateMaxTableBytes && ctx->d <= kGatherEstimateMaxD;
+    if (ctx->plan.mode == PLAN_BINNED && (ctx->tun.estimate_path == 2 || (ctx->tun.estimate_path == 0 && !small))) {
         bool done = false;
         SAMS_TRY(enqueue_estimates_planned_fused(ctx, S_mean, vhat, est, &done, hist));
         if (done) {

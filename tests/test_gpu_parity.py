@@ -29,50 +29,50 @@ PATHS = {  # how sketch_accumulate is carried out (sams_configure); results must
     "default": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
                     sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=2),
     "worker-major-staging": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16, scatter_threads=1024,
-                                 sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1,
+                                 sketch_path=0, estimate_path=2, fuse_head=0, stage_rows=0, fuse_median=1,
                                  stage_interleave=0, acc_wide=0),
     "binned-small-windows": dict(tile_log2=8, win_log2=6, chunk_log2=8, acc_threads=256, run_pad=4,
-                                 scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                                 scatter_threads=256, sketch_path=0, estimate_path=2, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "binned-ragged": dict(tile_log2=10, win_log2=9, chunk_log2=11, acc_threads=512, run_pad=32,
-                          scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=0, stage_interleave=0, acc_wide=0),
+                          scatter_threads=512, sketch_path=0, estimate_path=2, fuse_head=0, stage_rows=0, fuse_median=0, stage_interleave=0, acc_wide=0),
     "binned-unroll2": dict(tile_log2=12, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=16,
-                           scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                           scatter_threads=1024, sketch_path=0, estimate_path=2, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "global-atomic": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32,
-                          scatter_threads=1024, sketch_path=1, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                          scatter_threads=1024, sketch_path=1, estimate_path=2, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "lds-atomics": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32,
-                        scatter_threads=1024, sketch_path=3, estimate_path=0, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                        scatter_threads=1024, sketch_path=3, estimate_path=2, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "fused-head": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
-                       scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                       scatter_threads=1024, sketch_path=0, estimate_path=2, fuse_head=1, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "fused-head-small-tiles": dict(tile_log2=9, win_log2=7, chunk_log2=9, acc_threads=256, run_pad=8,
-                                   scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                                   scatter_threads=256, sketch_path=0, estimate_path=2, fuse_head=1, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "fused-head-per-worker": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=32,
-                                  scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
+                                  scatter_threads=1024, sketch_path=2, estimate_path=2, fuse_head=2, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "row-groups": dict(tile_log2=11, win_log2=9, chunk_log2=10, acc_threads=512, run_pad=32,
-                       scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=2, fuse_median=1, stage_interleave=0, acc_wide=0),
+                       scatter_threads=512, sketch_path=0, estimate_path=2, fuse_head=1, stage_rows=2, fuse_median=1, stage_interleave=0, acc_wide=0),
     "one-row-at-a-time": dict(tile_log2=12, win_log2=10, chunk_log2=10, acc_threads=1024, run_pad=16,
-                              scatter_threads=1024, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=1, fuse_median=1, stage_interleave=0, acc_wide=0),
+                              scatter_threads=1024, sketch_path=0, estimate_path=2, fuse_head=0, stage_rows=1, fuse_median=1, stage_interleave=0, acc_wide=0),
     "estimate-by-gathers": dict(tile_log2=14, win_log2=14, chunk_log2=10, acc_threads=1024, run_pad=32,
                                 scatter_threads=1024, sketch_path=0, estimate_path=1, fuse_head=0, stage_rows=0, fuse_median=1, stage_interleave=0, acc_wide=0),
     "interleaved-staging": dict(tile_log2=0, win_log2=0, chunk_log2=0, acc_threads=0, run_pad=16,
-                                scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0, fuse_median=1,
+                                scatter_threads=1024, sketch_path=2, estimate_path=2, fuse_head=2, stage_rows=0, fuse_median=1,
                                 stage_interleave=1, acc_wide=0),
     "interleaved-staging-row-groups": dict(tile_log2=11, win_log2=9, chunk_log2=8, acc_threads=256, run_pad=4,
-                                           scatter_threads=512, sketch_path=0, estimate_path=0, fuse_head=1, stage_rows=2,
+                                           scatter_threads=512, sketch_path=0, estimate_path=2, fuse_head=1, stage_rows=2,
                                            fuse_median=1, stage_interleave=1, acc_wide=0),
     "interleaved-staging-unfused": dict(tile_log2=10, win_log2=8, chunk_log2=11, acc_threads=512, run_pad=32,
-                                        scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0, stage_rows=0,
+                                        scatter_threads=256, sketch_path=0, estimate_path=2, fuse_head=0, stage_rows=0,
                                         fuse_median=0, stage_interleave=1, acc_wide=0),
     "accumulate-16-byte-loads": dict(tile_log2=12, win_log2=10, chunk_log2=11, acc_threads=1024, run_pad=8,
-                                     scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0,
+                                     scatter_threads=1024, sketch_path=2, estimate_path=2, fuse_head=2, stage_rows=0,
                                      fuse_median=1, stage_interleave=1, acc_wide=1),
     "chunk-records": dict(tile_log2=14, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=16,
-                          scatter_threads=1024, sketch_path=2, estimate_path=0, fuse_head=2, stage_rows=0,
+                          scatter_threads=1024, sketch_path=2, estimate_path=2, fuse_head=2, stage_rows=0,
                           fuse_median=1, stage_interleave=1, acc_wide=2),
     "chunk-records-worker-major": dict(tile_log2=13, win_log2=15, chunk_log2=11, acc_threads=1024, run_pad=32,
-                                       scatter_threads=512, sketch_path=2, estimate_path=0, fuse_head=0, stage_rows=2,
+                                       scatter_threads=512, sketch_path=2, estimate_path=2, fuse_head=0, stage_rows=2,
                                        fuse_median=1, stage_interleave=0, acc_wide=2),
     "accumulate-16-byte-loads-worker-major": dict(tile_log2=10, win_log2=8, chunk_log2=11, acc_threads=1024, run_pad=32,
-                                                  scatter_threads=256, sketch_path=0, estimate_path=0, fuse_head=0,
+                                                  scatter_threads=256, sketch_path=0, estimate_path=2, fuse_head=0,
                                                   stage_rows=2, fuse_median=1, stage_interleave=0, acc_wide=1),
 }
 
@@ -735,7 +735,7 @@ def test_a_context_keeps_the_tunables_it_was_created_with(sams):
         launches = {kn: cnt for kn, (_, cnt) in ctx.sams_profile_read().items()}
         return launches, host(S).copy(), host(idx).copy(), host(ed).copy()
 
-    first = dict(PATHS["default"], fuse_head=2, sketch_path=2, scatter_threads=512, estimate_path=0)
+    first = dict(PATHS["default"], fuse_head=2, sketch_path=2, scatter_threads=512, estimate_path=2)
     other = dict(PATHS["default"], fuse_head=0, sketch_path=1, scatter_threads=256, estimate_path=1, tile_log2=9,
                  win_log2=8, chunk_log2=8, acc_threads=256)
     try:

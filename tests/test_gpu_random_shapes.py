@@ -48,7 +48,7 @@ def sample(rng):
         tun["run_pad"] = int(rng.choice([4, 8, 16, 32]))
         tun["scatter_threads"] = int(rng.choice([256, 512, 1024]))
     tun["sketch_path"] = int(rng.choice([0, 0, 2, 2, 3, 1]))
-    tun["estimate_path"] = int(rng.choice([0, 0, 0, 1]))
+    tun["estimate_path"] = int(rng.choice([0, 2, 2, 1]))
     tun["fuse_head"] = int(rng.integers(0, 3))
     tun["fuse_median"] = int(rng.choice([1, 1, 0]))
     tun["stage_rows"] = int(rng.choice([0, 0, 1, 2, 3]))
