@@ -59,7 +59,7 @@ constexpr int kRecPadRanks = 256;              // dummy ranks of the padding pos
 constexpr int kRecMaxChain = 127;              // positions one chain may have
 constexpr int kRecWords = kRecCodeWords + kRecChains;
 constexpr uint32_t kCodeChain = 0x8000u, kCodeRankMask = 0x7ffu;
-constexpr int kRecDepth = 6;                   // chunks in flight per workgroup of k_bin_accumulate_r (even; 4 and 8 measured 3-5 % slower)
+constexpr int kRecDepth = 6;                   // chunks in flight per workgroup of k_bin_accumulate_r (even; 4, 6 and 8 time alike)
 
 // streaming accesses: data touched once per step should not push the shared metadata out of L2.
 // One 16-byte nontemporal instruction each (the pointers are 16-byte aligned, as float4 requires).
