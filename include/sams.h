@@ -147,8 +147,9 @@ int64_t sams_scratch_bytes(const sams_ctx *ctx);
  * free memory of the current device in 1 GiB blocks (up to `fraction` of it, 0 < fraction <= 1; stops early
  * when an allocation fails) and frees every block again.  Computes nothing and keeps nothing.  On MI355X
  * the memory manager places later allocations -- of this and of later processes -- differently afterwards, and
- * with that placement of the plan and the staging buffer the kernels of a step run 3 to 14 % faster (measured;
- * the cause is not established).  Synchronises the device.  Returns the number of GiB it held at the peak, or
+ * with that placement the kernels of a step run 3 to 14 % faster (measured; the cause is not established).  It
+ * has to come first: a process that makes the pass after it has allocated its own buffers, or after sams_create,
+ * stays as slow as one that never makes it.  Synchronises the device.  Returns the number of GiB it held at the peak, or
  * a negative code (SAMS_EINVAL for a fraction out of range, SAMS_EHIP).
  */
 int64_t sams_precondition_device_memory(double fraction);
