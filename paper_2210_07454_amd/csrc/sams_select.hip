@@ -342,38 +342,32 @@ k_sel_write(const float *__restrict__ est, int64_t d, const SelState *__restrict
                  est_sel);
 }
 
-// The whole selection in one workgroup of 1024 threads for len <= kSelSmallMax keys: the three histogram passes
-// with their digit picks, the counts per segment of kSelSmallSeg keys (one wavefront each), their prefixes, and
-// the ordered compaction.  Same arithmetic as the kernels above; replaces ten launches, which is most of the
-// step's time when the vector has only tens of thousands of coordinates.  (Its 43 us at 65,536 keys are the
-// instruction issue of one compute unit -- counts and ordered compaction 23 us, the second and third pass 7 us each,
-// the first 5 us: four counters per histogram bin, the keys kept in registers across the phases, or the loads of
-// eight sweeps issued together each change nothing.)
+// The whole selection in one workgroup of 1024 threads for len <= kSelSmallMax keys: the histogram of the first
+// digit with its pick, one sweep that lists the keys sharing that digit in LDS (the later digits, and the counts at
+// the threshold per segment of kSelSmallSeg keys, then come from the list), prefixes, and the ordered compaction (one
+// wavefront per segment).  Same arithmetic as the kernels above; replaces ten launches, which is most of the step's
+// time when the vector has only tens of thousands of coordinates.  Its time is the instruction issue of one compute
+// unit, about 5 us per sweep over 65,536 keys plus 10 us for the compaction: three sweeps instead of five brought it
+// from 40 to 32 us; four counters per histogram bin, the keys kept in registers across the phases, or the loads of
+// eight sweeps issued together each changed nothing.
+constexpr int kSmallCand = 8192;             // keys sharing the threshold's first digit that the one-workgroup selection can list in LDS
 __global__ void __launch_bounds__(1024)
 k_sel_small(const float *__restrict__ keys, int64_t len, uint32_t k, int32_t *__restrict__ idx,
             float *__restrict__ val_sel)
 {
     __shared__ uint32_t lh[kHistBins];
+    __shared__ uint32_t cand[kSmallCand];                            // (segment << 20) | low 20 bits of a listed key
+    __shared__ uint32_t ncand;
     __shared__ uint32_t part[16];
     __shared__ uint32_t sh[2];                                       // prefix, k_rem after a pick
     __shared__ uint32_t seg_gt[16], seg_eq[16], seg_sel_base[16], seg_eq_base[16];
     const int t = threadIdx.x;
+    const int lane = t & (kWave - 1), seg = t / kWave;               // 16 wavefronts, one segment of the keys each
+    const int64_t base = (int64_t)seg * kSelSmallSeg;
     uint32_t prefix = 0, k_rem = k;
-    for (int pass = 0; pass < kSelPasses; ++pass) {
-        const int shift = sel_shift(pass), width = sel_width(pass);
-        const uint32_t dmask = (1u << width) - 1u;
-        for (int b = t; b < kHistBins; b += 1024) lh[b] = 0;
-        __syncthreads();
-        for (int64_t l = (int64_t)t * 4; l < len; l += 4096) {
-            const Keys4 q = load_keys4(keys, l, len);
-#pragma unroll
-            for (int z = 0; z < 4; ++z) {
-                const uint32_t key = mag_key(q.v[z]);
-                if (((q.have >> z) & 1u) && (key >> (shift + width)) == prefix)
-                    atomicAdd(&lh[(key >> shift) & dmask], 1u);
-            }
-        }
-        __syncthreads();
+    // lh holds the histogram of the next `width` bits over the keys whose higher bits equal prefix: find the bin of
+    // the k_rem-th largest, extend the prefix by it
+    auto pick = [&](int width) {
         const int nb = 1 << width;
         const int b0 = nb - 1 - 2 * t, b1 = nb - 2 - 2 * t;          // descending bins, two per thread
         const uint32_t v0 = b0 >= 0 ? lh[b0] : 0u, v1 = b1 >= 0 ? lh[b1] : 0u;
@@ -390,16 +384,90 @@ k_sel_small(const float *__restrict__ keys, int64_t len, uint32_t k, int32_t *__
         prefix = sh[0];
         k_rem = sh[1];
         __syncthreads();
+    };
+    auto clear_hist = [&]() {
+        for (int b = t; b < kHistBins; b += 1024) lh[b] = 0;
+        __syncthreads();
+    };
+    auto hist_over_keys = [&](int pass) {
+        const int shift = sel_shift(pass), width = sel_width(pass);
+        const uint32_t dmask = (1u << width) - 1u;
+        clear_hist();
+        for (int64_t l = (int64_t)t * 4; l < len; l += 4096) {
+            const Keys4 q = load_keys4(keys, l, len);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const uint32_t key = mag_key(q.v[z]);
+                if (((q.have >> z) & 1u) && (key >> (shift + width)) == prefix)
+                    atomicAdd(&lh[(key >> shift) & dmask], 1u);
+            }
+        }
+        __syncthreads();
+    };
+    hist_over_keys(0);
+    if (t == 0) ncand = 0;
+    pick(sel_width(0));                                              // its barriers also publish ncand = 0
+    // One sweep lists the keys that share the threshold's first digit (few, unless many keys are equal) and counts, per
+    // segment, the keys above that digit; the last two digits and the counts at the threshold then come from the
+    // list instead of from three more sweeps over all keys.
+    {
+        uint32_t ngt = 0;
+        for (int s = 0; s < kSelSmallSeg; s += kWave * 4) {
+            const Keys4 q = load_keys4(keys, base + s + lane * 4, len);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const uint32_t key = mag_key(q.v[z]);
+                if ((q.have >> z) & 1u) {
+                    const uint32_t top = key >> sel_shift(0);
+                    ngt += top > prefix ? 1u : 0u;
+                    if (top == prefix) {
+                        const uint32_t slot = atomicAdd(&ncand, 1u);
+                        if (slot < (uint32_t)kSmallCand) cand[slot] = ((uint32_t)seg << 20) | (key & 0xFFFFFu);
+                    }
+                }
+            }
+        }
+        uint32_t zero = 0;
+        wave_sum2(ngt, zero);
+        if (lane == 0) {
+            seg_gt[seg] = ngt;
+            seg_eq[seg] = 0;
+        }
+    }
+    __syncthreads();
+    const uint32_t listed = ncand;
+    if (listed <= (uint32_t)kSmallCand) {
+        clear_hist();
+        for (uint32_t q = t; q < listed; q += 1024) atomicAdd(&lh[(cand[q] >> 10) & 1023u], 1u);
+        __syncthreads();
+        pick(sel_width(1));
+        const uint32_t digit1 = prefix & 1023u;
+        clear_hist();
+        for (uint32_t q = t; q < listed; q += 1024) {
+            const uint32_t e = cand[q];
+            if (((e >> 10) & 1023u) == digit1) atomicAdd(&lh[e & 1023u], 1u);
+        }
+        __syncthreads();
+        pick(sel_width(2));
+        const uint32_t tau20 = prefix & 0xFFFFFu;
+        for (uint32_t q = t; q < listed; q += 1024) {
+            const uint32_t e = cand[q], low = e & 0xFFFFFu;
+            if (low > tau20) atomicAdd(&seg_gt[e >> 20], 1u);
+            if (low == tau20) atomicAdd(&seg_eq[e >> 20], 1u);
+        }
+    } else {                                                         // too many to list: sweeps over all keys
+        hist_over_keys(1);
+        pick(sel_width(1));
+        hist_over_keys(2);
+        pick(sel_width(2));
+        uint32_t ngt = 0, neq = 0;
+        if (base < len) wave_count(keys, len, base, kSelSmallSeg, prefix, lane, &ngt, &neq);
+        if (lane == 0) {
+            seg_gt[seg] = ngt;
+            seg_eq[seg] = neq;
+        }
     }
     const uint32_t tau = prefix, k_eq = k_rem;
-    const int lane = t & (kWave - 1), seg = t / kWave;               // 16 wavefronts, one segment each
-    const int64_t base = (int64_t)seg * kSelSmallSeg;
-    uint32_t ngt = 0, neq = 0;
-    if (base < len) wave_count(keys, len, base, kSelSmallSeg, tau, lane, &ngt, &neq);
-    if (lane == 0) {
-        seg_gt[seg] = ngt;
-        seg_eq[seg] = neq;
-    }
     __syncthreads();
     if (t == 0) {
         uint32_t eb = 0, sb = 0;

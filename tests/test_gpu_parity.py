@@ -430,6 +430,31 @@ def test_topk_refine_bit_exact_with_ties(sams, k_in, k_out):
         assert np.array_equal(host(io), idx) and np.array_equal(host(do), delta)
 
 
+@pytest.mark.parametrize("in_bin", [1, 700, 8191, 8192, 8193, 20_000, 60_000])
+@pytest.mark.parametrize("k_in", [60_000, 65_536, 4_100])
+def test_one_workgroup_selection_around_the_capacity_of_its_candidate_list(sams, k_in, in_bin):
+    """Selection of short vectors (one workgroup): the keys that share the first radix digit of the threshold are
+    listed in LDS when at most 8192 do, otherwise the later digits come from sweeps over all keys.  `in_bin` keys
+    lie in [1.5, 1.625) (one value of the first digit), 300 above, the rest far below; the threshold falls among the
+    `in_bin`, with exact ties among them."""
+    in_bin = min(in_bin, k_in - 300)
+    rng = np.random.default_rng(k_in + in_bin)
+    vals = (rng.uniform(0.001, 0.1, k_in) * rng.choice([-1.0, 1.0], k_in)).astype(np.float32)
+    where = rng.permutation(k_in)
+    vals[where[:300]] = rng.uniform(2.0, 9.0, 300).astype(np.float32)
+    grid = (1.5 + rng.integers(0, 64, in_bin) / 512.0).astype(np.float32)          # 64 distinct values: many ties
+    vals[where[300:300 + in_bin]] = grid * rng.choice([-1.0, 1.0], in_bin).astype(np.float32)
+    cand = np.arange(k_in, dtype=np.int32) * 3
+    o = Oracle("f32")
+    with sams.Context(3 * k_in, 2, 3, 1000, k_in, inputs.hash_params(3)) as ctx:
+        for k_out in sorted({300 + max(1, in_bin // 2), 300 + in_bin, 301, min(k_in, 300 + in_bin + 5)}):
+            idx, delta = o.refine(cand, vals, k_out)
+            io = torch.full((k_out,), -1, device="cuda", dtype=torch.int32)
+            do = torch.empty(k_out, device="cuda")
+            ctx.topk_refine(dev(cand), dev(vals), k_out, io, do)
+            assert np.array_equal(host(io), idx) and np.array_equal(host(do), delta), k_out
+
+
 @pytest.mark.parametrize("wl,d,P", [("C4", 400_000, 4), ("P1", 600_000, 8), ("P2a", 60_000, 4)])
 def test_chained_steps_with_overselection_follow_the_oracle(sams, wl, d, P):
     """The paper's second round (Sec. III-A) with P*k candidates: context created with k = P*k, top-k refined
