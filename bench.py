@@ -164,7 +164,7 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="time the K steps as one replay of a HIP graph captured from them (for small, launch-bound "
                          "workloads); the per-kernel figures then come from an eager pass of K steps run before it")
-    ap.add_argument("--tune", default="fuse_head=2",
+    ap.add_argument("--tune", default="fuse_head=2,stage_spread=1",
                     help="library tunables (sams_configure), e.g. fuse_head=1,tile_log2=14,win_log2=15")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -103,6 +103,14 @@ int sams_create(sams_ctx **out, int64_t d, int32_t n, int32_t r, int64_t c, int6
  *                 32 stream positions lie next to each other (one 128-byte line each), so that the workgroups of the
  *                 workers, which run side by side, write and read one region per (row, window) instead of n distant
  *                 ones.  Same results either way (at d = 124M the contiguous layout is 2 % faster as a whole step).
+ *   "stage_spread" 0 (default) or 1: with 1, sams_create maps a staging buffer of 2 GiB or more from 1 GiB physical chunks
+ *                 picked at even distances over all free device memory, instead of taking one allocation.  Device
+ *                 memory is striped over the HBM stacks in coarse pieces, so a buffer that is contiguous in physical
+ *                 memory reaches only part of them; scattered over all of it, it reaches all (the first sketch pass is
+ *                 20 % faster than with the contiguous buffer a fresh process gets, and no slower than after
+ *                 sams_precondition_device_memory).  To pick the chunks sams_create holds nearly all free device
+ *                 memory for a moment -- other allocations made on the device meanwhile can fail -- and falls back to
+ *                 the ordinary allocation when it cannot.  Same results.
  *   "acc_wide"    2 (default), 1 or 0: with 1024 threads and 2048-position chunks the binned accumulation reads its
  *                 streams with 16-byte loads instead of 4-byte loads (1, 2), and with 2 the per-position metadata
  *                 (4 bytes) is replaced by per-chunk records (2-byte codes plus a list of the groups of positions
@@ -150,7 +158,8 @@ int64_t sams_scratch_bytes(const sams_ctx *ctx);
  * with that placement the kernels of a step run 3 to 14 % faster (measured: memory that is contiguous in physical
  * address reaches only part of the HBM stacks, memory scattered over all of it reaches all of them).  It
  * has to come first: a process that makes the pass after it has allocated its own buffers, or after sams_create,
- * stays as slow as one that never makes it.  Synchronises the device.  Returns the number of GiB it held at the peak, or
+ * stays as slow as one that never makes it.  ("stage_spread" gives the context's staging buffer, the one buffer the
+ * effect hinges on, the scattered placement whatever came before.)  Synchronises the device.  Returns the number of GiB it held at the peak, or
  * a negative code (SAMS_EINVAL for a fraction out of range, SAMS_EHIP).
  */
 int64_t sams_precondition_device_memory(double fraction);

@@ -10,7 +10,7 @@
 namespace sams {
 
 int g_last_hip_error = 0;
-Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 0, 2};
+Tunables g_tun = {0, 0, 0, 0, 0, 1024, 0, 0, 1, 0, 16, 0, 0, 2};
 static std::mutex g_tun_mutex;      // sams_configure against the copy sams_create takes
 
 static const char *const kKernelNames[KID_COUNT] = {
@@ -210,6 +210,9 @@ int sams_configure(const char *key, int value)
     } else if (!strcmp(key, "stage_interleave")) {
         if (value < 0 || value > 1) return SAMS_EINVAL;
         g_tun.stage_interleave = value;
+    } else if (!strcmp(key, "stage_spread")) {
+        if (value < 0 || value > 1) return SAMS_EINVAL;
+        g_tun.stage_spread = value;
     } else if (!strcmp(key, "acc_wide")) {
         if (value < 0 || value > 2) return SAMS_EINVAL;
         g_tun.acc_wide = value;

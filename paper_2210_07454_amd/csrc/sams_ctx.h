@@ -77,6 +77,8 @@ struct Plan {
     uint32_t *meta;     // [r][rowlen]          per stream position: bucket in window, chain link, flags (absent with acc_variant 2)
     uint32_t *rec;      // [r][rowlen/4096][2560] chunk records of acc_variant 2: 4096 16-bit codes, 512 chain entries
     uint16_t *wlow;     // [r][rowlen]          per stream position: bucket in window only (what the recovery reads)
+    void *stg_chunks;   // staging mapped from physical chunks picked all over device memory (stage_spread): their handles, else null
+    int64_t stg_nchunks, stg_va_bytes;
     float *stg;         // n * stage_rows * rowlen floats: per-step staging, signed values at their stream positions
                         //                      ([stage_rows][rowlen/32][n][32], or [n][stage_rows][rowlen] without stage_ilv)
     const float *staged_u;  // vector whose sorted copy the staging holds (set by a fused head), else null
@@ -100,6 +102,7 @@ struct Tunables {
     int stage_rows;       // rows staged at once (0 = all r): bounds the staging buffer at n*stage_rows*rowlen floats
     int run_pad;          // runs are padded to a multiple of this many stream positions (4, 8, 16 or 32)
     int stage_interleave; // 1 = the workers' staged copies are interleaved in pieces of 32 stream positions
+    int stage_spread;     // 1 = a staging buffer of 2 GiB or more is mapped from 1 GiB chunks picked at even distances over all free device memory
     int acc_wide;         // accumulate kernel where its shape allows (1024 threads, 2048-position chunks): 1 = 16-byte loads,
                           // 2 = 16-byte loads and compact chunk records instead of meta words (falls back to 1 when a chunk has too many chains)
 };

@@ -1435,6 +1435,110 @@ k_sketch_lds(const float *__restrict__ u, float *__restrict__ S, HashParams hp, 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+// The staging buffer as one range of virtual addresses backed by 1 GiB physical chunks picked at even distances over
+// all free device memory.  Device memory is striped over the HBM stacks in coarse pieces: a buffer that is contiguous in
+// physical memory reaches only part of the stacks (scattered 512-byte writes into it run at 5.4 TB/s), one scattered
+// over all of physical memory reaches all (7.2 TB/s).  To pick the chunks the call holds nearly all free memory for a
+// moment: every chunk the device can give is created, the wanted ones are mapped, the others released.
+static void spread_free(Plan &pl)
+{
+    if (!pl.stg_chunks) return;
+    hipMemGenericAllocationHandle_t *h = static_cast<hipMemGenericAllocationHandle_t *>(pl.stg_chunks);
+    if (pl.stg) {
+        (void)hipMemUnmap(pl.stg, (size_t)pl.stg_va_bytes);
+        (void)hipMemAddressFree(pl.stg, (size_t)pl.stg_va_bytes);
+    }
+    for (int64_t q = 0; q < pl.stg_nchunks; ++q) (void)hipMemRelease(h[q]);
+    delete[] h;
+    pl.stg_chunks = nullptr;
+    pl.stg = nullptr;
+    pl.stg_nchunks = pl.stg_va_bytes = 0;
+}
+
+// SAMS_OK with pl.stg set, or SAMS_ENOMEM with nothing held (the caller then takes an ordinary allocation)
+static int spread_alloc(sams_ctx *ctx, int64_t bytes)
+{
+    Plan &pl = ctx->plan;
+    const size_t chunk = (size_t)1 << 30;
+    const int64_t need = (int64_t)(((size_t)bytes + chunk - 1) / chunk);
+    int dev = 0;
+    size_t free_b = 0, total_b = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipMemGetInfo(&free_b, &total_b) != hipSuccess) {
+        (void)hipGetLastError();
+        return SAMS_ENOMEM;
+    }
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = dev;
+    size_t gran = 0;
+    if (hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityRecommended) != hipSuccess || gran == 0 ||
+        chunk % gran != 0) {
+        (void)hipGetLastError();
+        return SAMS_ENOMEM;
+    }
+    const int64_t most = (int64_t)((double)free_b * 0.97 / (double)chunk);
+    if (most < need) return SAMS_ENOMEM;
+    hipMemGenericAllocationHandle_t *all = new (std::nothrow) hipMemGenericAllocationHandle_t[most];
+    hipMemGenericAllocationHandle_t *kept = new (std::nothrow) hipMemGenericAllocationHandle_t[need];
+    if (!all || !kept) {
+        delete[] all;
+        delete[] kept;
+        return SAMS_ENOMEM;
+    }
+    int64_t made = 0;
+    for (; made < most; ++made)
+        if (hipMemCreate(&all[made], chunk, &prop, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            break;
+        }
+    void *va = nullptr;
+    bool ok = made >= need && hipMemAddressReserve(&va, (size_t)need * chunk, 0, nullptr, 0) == hipSuccess;
+    int64_t mapped = 0;
+    if (ok) {
+        for (int64_t q = 0, next = 0; q < made; ++q) {
+            const int64_t want = next < need ? (next * made + made / 2) / need : -1;   // evenly spaced, centred
+            if (q == want) {
+                kept[next] = all[q];
+                if (ok && hipMemMap(static_cast<char *>(va) + (size_t)next * chunk, chunk, 0, all[q], 0) == hipSuccess)
+                    ++mapped;
+                else
+                    ok = false;
+                ++next;
+            } else {
+                (void)hipMemRelease(all[q]);
+            }
+        }
+        if (ok) {
+            hipMemAccessDesc ad = {};
+            ad.location = prop.location;
+            ad.flags = hipMemAccessFlagsProtReadWrite;
+            ok = hipMemSetAccess(va, (size_t)need * chunk, &ad, 1) == hipSuccess;
+        }
+        if (!ok) {
+            (void)hipGetLastError();
+            if (mapped) (void)hipMemUnmap(va, (size_t)mapped * chunk);
+            for (int64_t q = 0; q < need; ++q) (void)hipMemRelease(kept[q]);
+            (void)hipMemAddressFree(va, (size_t)need * chunk);
+        }
+    } else {
+        (void)hipGetLastError();
+        for (int64_t q = 0; q < made; ++q) (void)hipMemRelease(all[q]);
+        if (va) (void)hipMemAddressFree(va, (size_t)need * chunk);
+    }
+    delete[] all;
+    if (!ok) {
+        delete[] kept;
+        return SAMS_ENOMEM;
+    }
+    pl.stg = static_cast<float *>(va);
+    pl.stg_chunks = kept;
+    pl.stg_nchunks = need;
+    pl.stg_va_bytes = (int64_t)((size_t)need * chunk);
+    ctx->scratch_bytes += pl.stg_va_bytes;
+    return SAMS_OK;
+}
+
 static int dev_alloc(sams_ctx *ctx, void **p, int64_t bytes)
 {
     hipError_t e = hipMalloc(p, (size_t)(bytes > 0 ? bytes : 4));
@@ -1716,7 +1820,9 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
             if (e == hipSuccess) e = hipGetLastError();
             if (e != hipSuccess) { g_last_hip_error = (int)e; rc = SAMS_EHIP; break; }
         }
-        rc = dev_alloc(ctx, (void **)&pl.stg, n * pl.stage_rows * rowlen * 4);
+        const int64_t stg_bytes = n * pl.stage_rows * rowlen * 4;
+        rc = (tun.stage_spread && stg_bytes >= ((int64_t)2 << 30)) ? spread_alloc(ctx, stg_bytes) : SAMS_ENOMEM;
+        if (rc != SAMS_OK) rc = dev_alloc(ctx, (void **)&pl.stg, stg_bytes);
         // the median is fused when a thread can hold the row estimates of its coordinates and the staging
         // buffer can hold the looked-up values of all r rows; otherwise they go through rowest
         pl.fused_median = tun.fuse_median && fused_median_iters(ctx->r, pl.tile_log2) > 0 && (ctx->d & 3) == 0 &&
@@ -1735,6 +1841,7 @@ int plan_create(sams_ctx *ctx, const Tunables &tun)
 void plan_destroy(sams_ctx *ctx)
 {
     Plan &pl = ctx->plan;
+    spread_free(pl);                                                 // leaves pl.stg null when it was mapped from chunks
     void *ptrs[] = {pl.srcp, pl.dst16, pl.pbase, pl.binbase, pl.meta, pl.rec, pl.wlow, pl.stg, pl.rowest};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);

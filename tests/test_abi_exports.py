@@ -63,10 +63,10 @@ def test_configure_rejects_unknown_keys_and_bad_values_without_a_gpu():
     lib = sams.load()
     ok = [(b"tile_log2", 14), (b"tile_log2", 0), (b"win_log2", 15), (b"win_log2", 0), (b"chunk_log2", 0), (b"acc_threads", 0),
           (b"run_pad", 32), (b"run_pad", 16), (b"scatter_threads", 1024), (b"sketch_path", 0), (b"estimate_path", 2), (b"estimate_path", 0),
-          (b"fuse_head", 0), (b"fuse_median", 1), (b"stage_rows", 0)]
+          (b"fuse_head", 0), (b"fuse_median", 1), (b"stage_rows", 0), (b"stage_spread", 1), (b"stage_spread", 0)]
     bad = [(b"tile_log2", 15), (b"tile_log2", 5), (b"win_log2", 16), (b"win_log2", 3), (b"chunk_log2", 12),
            (b"acc_threads", 384), (b"run_pad", 5), (b"scatter_threads", 100), (b"sketch_path", 4),
-           (b"estimate_path", -1), (b"estimate_path", 3), (b"fuse_head", 3), (b"stage_rows", 17), (b"no_such_key", 1)]
+           (b"estimate_path", -1), (b"estimate_path", 3), (b"stage_spread", 2), (b"fuse_head", 3), (b"stage_rows", 17), (b"no_such_key", 1)]
     for key, val in bad:
         assert lib.sams_configure(key, val) == sams.SAMS_EINVAL, (key, val)
     assert lib.sams_configure(None, 0) == sams.SAMS_EINVAL

@@ -43,6 +43,7 @@ def test_full_size_second_iteration_matches_oracle(wl, full_sort, sketch_workers
     w = inputs.WORKLOADS[wl]
     d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
     sams.sams_configure("fuse_head", 2)
+    sams.sams_configure("stage_spread", 1)
     try:
         gs = inputs.GradientStream(w, device="cuda")
         hp = inputs.hash_params(r, seed=w.seed)
@@ -102,6 +103,7 @@ def test_full_size_second_iteration_matches_oracle(wl, full_sort, sketch_workers
             assert np.array_equal(host(b.x), st["x"]) and np.array_equal(host(b.e_u), st["e"])
     finally:
         sams.sams_configure("fuse_head", 0)
+        sams.sams_configure("stage_spread", 0)
 
 
 @pytest.mark.timeout(900)
@@ -115,6 +117,7 @@ def test_full_size_variants_parameter_averaging_and_second_round(wl, P):
     d, n, r, c, k = w.d, w.n, w.r, w.c, w.k
     kc = P * k
     sams.sams_configure("fuse_head", 2)
+    sams.sams_configure("stage_spread", 1)
     try:
         gs = inputs.GradientStream(w, device="cuda")
         hp = inputs.hash_params(r, seed=w.seed)
@@ -160,6 +163,7 @@ def test_full_size_variants_parameter_averaging_and_second_round(wl, P):
             assert np.array_equal(host(b.S_workers[0]), o.sketch(st["e"][0], hp, c))
     finally:
         sams.sams_configure("fuse_head", 0)
+        sams.sams_configure("stage_spread", 0)
 
 
 @pytest.mark.timeout(1500)
@@ -179,7 +183,7 @@ def test_stress_size_second_iteration_sampled(capfd):
     free, total = torch.cuda.mem_get_info()
     if total < 250 * 2**30:
         pytest.skip("needs a 288 GB device")
-    tun = dict(fuse_head=2, stage_rows=2, run_pad=16)
+    tun = dict(fuse_head=2, stage_rows=2, run_pad=16, stage_spread=1)
     for key, val in tun.items():
         sams.sams_configure(key, val)
     try:
@@ -258,5 +262,5 @@ def test_stress_size_second_iteration_sampled(capfd):
             assert not host(b.e_u[:, il].contiguous()).any()
             say("gather and tail checked")
     finally:
-        for key, val in dict(fuse_head=0, stage_rows=0, run_pad=16).items():
+        for key, val in dict(fuse_head=0, stage_rows=0, run_pad=16, stage_spread=0).items():
             sams.sams_configure(key, val)

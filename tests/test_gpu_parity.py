@@ -784,6 +784,44 @@ def test_a_context_keeps_the_tunables_it_was_created_with(sams):
             sams.sams_configure(key, val)
 
 
+def test_staging_mapped_from_scattered_chunks_gives_the_same_tables_and_returns_its_memory(sams):
+    """"stage_spread": a staging buffer of 2 GiB or more mapped from 1 GiB physical chunks picked all over the free device
+    memory.  Same tables as with one allocation (which the full-size tests hold against the oracle), bit for bit, for a
+    fused head and for a plain sketch_accumulate; destroying the context gives every chunk back."""
+    d, n, r, c, k = 13_000_000, 8, 5, 262_144, 1000
+    hp = inputs.hash_params(r, seed=5)
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    g = torch.randn(n, d, device="cuda", generator=gen) * 1e-2
+    tables = {}
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free_before = torch.cuda.mem_get_info()[0]
+    try:
+        for spread in (0, 1):
+            for key, val in dict(PATHS["default"], fuse_head=2, sketch_path=2, stage_spread=spread).items():
+                sams.sams_configure(key, val)
+            with sams.Context(d, n, r, c, k, hp) as ctx:
+                assert ctx.scratch_bytes > (2 << 30)
+                b = sams.Buffers(d, n, r, c, k, 1e-8, torch.zeros(d, device="cuda"))
+                ctx.amsgrad_ef_update(g, b.m, b.e_u, b.v, b.vhat, b.x, None, None, 0, 0.9, 0.99, 1e-3)
+                ctx.sketch_accumulate(b.e_u, b.S_workers)                   # from the copy the head staged
+                first = host(b.S_workers).copy()
+                est = torch.empty(d, device="cuda")
+                ctx.sketch_reduce(b.S_workers, b.S_mean)
+                ctx.unsketch_estimates(b.S_mean, b.vhat, est)               # the recovery works through the staging buffer
+                ctx.sketch_accumulate(b.e_u, b.S_workers)                   # both passes again
+                assert np.array_equal(host(b.S_workers), first)
+                tables[spread] = (first, host(est).copy())
+                del b, est
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            assert abs(torch.cuda.mem_get_info()[0] - free_before) <= (64 << 20), spread
+        assert np.array_equal(tables[0][0], tables[1][0]) and np.array_equal(tables[0][1], tables[1][1])
+    finally:
+        for key, val in dict(PATHS["default"], stage_spread=0).items():
+            sams.sams_configure(key, val)
+
+
 def test_invalid_arguments_are_rejected_without_launching(sams):
     hp = inputs.hash_params(5)
     bad = [dict(d=0), dict(k=0), dict(k=1001), dict(r=17), dict(c=0), dict(n=0), dict(d=inputs.P31)]
